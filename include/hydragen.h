@@ -1,0 +1,160 @@
+/*
+ * hydragen.h - C ABI of the MI355X (gfx950) shared-prefix decode-attention library.
+ *
+ * The library computes exact softmax attention for a batch of decode queries
+ * whose KV caches share prefixes, the way the Hydragen paper (arXiv 2402.05099)
+ * states the problem:
+ *
+ *   - attention over ONE shared KV block, batched across all sequences' queries
+ *     into a matrix-matrix product (Sec. 3.2, inter-sequence batching);
+ *   - attention over each sequence's own ragged suffix KV (Sec. 3.2, last
+ *     paragraph: computed per sequence, one query each);
+ *   - each part returns its output and the log-sum-exp of its scaled scores
+ *     (Eq. 4), and parts are merged with LSE weights into the exact
+ *     full-context result (Eq. 5, proved in App. A);
+ *   - the same at every vertex of a tree of shared blocks (Sec. 3.3).
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates or frees device memory after hg_create, never copies to
+ *     or from the host, and never synchronises the host: work is enqueued on
+ *     the context's stream and the call returns.  Arrays of lengths/offsets are
+ *     read on the device, so their values may change between calls without any
+ *     host work.  Scalar shape arguments are host values.
+ *   - Layouts (row-major, innermost last), following the shapes in the
+ *     docstring of App. B's attention routine with num_queries = 1:
+ *       Q        bf16 [B, Hq, D]        one decode query per sequence
+ *       K, V     bf16 [rows, Hkv, D]    a shared block stored once, or packed suffix rows
+ *       O        [B, Hq, D]             fp32 or bf16 (o_dtype), LSE fp32 [B, Hq], natural log
+ *     Query head h uses KV head h / (Hq / Hkv) (grouped-query attention).
+ *   - An empty key set is legal everywhere: that part is O = 0, LSE = -inf and
+ *     has weight zero in a merge; a row whose parts are all empty is O = 0,
+ *     LSE = -inf.  (The paper is silent on empty parts.)
+ *   - No causal mask: the decode query attends to every listed key
+ *     (its own K/V row is expected to be the last suffix row already).
+ *   - scale <= 0 selects 1/sqrt(D) (Eq. 1).
+ *   - Supported: D in {64, 128}; Hq % Hkv == 0; B*Hq*D < 2^31; rows*Hkv*D < 2^31 per tensor.
+ *   - Every call returns HG_OK or an error code; on error nothing is enqueued
+ *     and outputs are untouched.  No C++ exception crosses this boundary.
+ *   - Calls on one context must not overlap in time from several host threads.
+ */
+#ifndef HYDRAGEN_H
+#define HYDRAGEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hg_ctx hg_ctx;
+
+enum { HG_OK = 0, HG_ERR_INVALID_ARG = 1, HG_ERR_UNSUPPORTED = 2, HG_ERR_WORKSPACE = 3, HG_ERR_HIP = 4 };
+enum { HG_F32 = 0, HG_BF16 = 1 };
+enum { HG_MAX_LEVELS = 4, HG_MAX_PARTS = 64 };
+
+/* Tunables for hg_set_option (0 = library default). */
+enum {
+    HG_OPT_PREFIX_SPLITS = 1, /* number of key-range splits of each shared block (>=1) */
+    HG_OPT_SUFFIX_CHUNK = 2,  /* keys per work item of the suffix kernel (multiple of 32) */
+    HG_OPT_OVERLAP = 3,       /* 1: run shared-block and suffix kernels on two streams inside the fused call */
+    HG_OPT_NAIVE_CHUNK = 4    /* keys per work item of the non-decomposed comparison kernel */
+};
+
+/*
+ * Create a context bound to `device`, enqueueing on `hip_stream` (a hipStream_t, NULL = default stream).
+ * `workspace` is caller-owned device memory of `workspace_bytes` bytes (256-byte aligned) that the
+ * library uses for partial (O, LSE) results; it must stay valid until hg_destroy and must not be shared
+ * by contexts used concurrently.  See hg_workspace_bytes.
+ */
+int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_t workspace_bytes);
+void hg_destroy(hg_ctx* ctx);
+int hg_set_stream(hg_ctx* ctx, void* hip_stream);
+int hg_set_option(hg_ctx* ctx, int option, int value);
+
+/*
+ * Bytes of workspace that hold `parts` fp32 partial results for B*Hq query rows: parts * B*Hq * (D+1) * 4,
+ * rounded up to 256.  Every call needs room for at least (number of shared levels + 1) parts; more room
+ * lets the library split long key ranges over more workgroups.  Pure host function.
+ */
+size_t hg_workspace_bytes(int B, int Hq, int D, int parts);
+
+/*
+ * Attention of every query over ONE shared KV block (Sec. 3.2): all B*Hq/Hkv query rows that use a KV head
+ * are stacked into one matrix against that head's P keys.  P == 0 is legal.
+ *   Kp, Vp : bf16 [P, Hkv, D];  O : [B, Hq, D] of o_dtype;  LSE : fp32 [B, Hq].
+ */
+int hg_prefix_attn(hg_ctx* ctx, const void* Q, const void* Kp, const void* Vp,
+                   int B, int Hq, int Hkv, int D, int P, float scale,
+                   void* O, int o_dtype, float* LSE);
+
+/*
+ * One level of a sharing tree (Sec. 3.3): n_blocks shared blocks stored back to back in K/V.
+ * Block g owns KV rows [kv_off[g], kv_off[g+1]) and is attended to by the contiguous sequences
+ * [seq_off[g], seq_off[g+1]) (sequences are in tree order).  kv_off/seq_off are DEVICE int32[n_blocks+1],
+ * non-decreasing.  max_rows / max_seqs are host upper bounds on rows and sequences per block; a block
+ * exceeding them is truncated.  With n_blocks == 1 both arrays may be NULL: the block is then rows
+ * [0, max_rows) shared by sequences [0, B).  Sequences not covered by any block get O = 0, LSE = -inf.
+ */
+typedef struct {
+    const void* K;
+    const void* V;
+    int n_blocks;
+    const int32_t* kv_off;
+    const int32_t* seq_off;
+    int max_rows;
+    int max_seqs;
+} hg_level;
+
+int hg_prefix_attn_grouped(hg_ctx* ctx, const void* Q, const hg_level* level,
+                           int B, int Hq, int Hkv, int D, float scale,
+                           void* O, int o_dtype, float* LSE);
+
+/*
+ * Per-sequence attention over ragged suffix KV (Sec. 3.2, last paragraph).  Sequence b owns rows
+ * [offsets[b], offsets[b] + lengths[b]) of Ks/Vs (bf16 [T, Hkv, D]); offsets/lengths are DEVICE int32[B];
+ * a padded [B, Lmax, Hkv, D] cache is offsets[b] = b * Lmax.  lengths[b] == 0 is legal; lengths above
+ * max_len (a host upper bound) are truncated to max_len.
+ */
+int hg_suffix_attn(hg_ctx* ctx, const void* Q, const void* Ks, const void* Vs,
+                   const int32_t* offsets, const int32_t* lengths, int max_len,
+                   int B, int Hq, int Hkv, int D, float scale,
+                   void* O, int o_dtype, float* LSE);
+
+/*
+ * n-way LSE merge (Eq. 5 generalised; App. B gives the two-part form):
+ *   m = max_i LSE_i;  w_i = exp(LSE_i - m);  O = sum_i w_i O_i / sum_i w_i;  LSE = m + log sum_i w_i.
+ * O_parts / LSE_parts are HOST arrays of n device pointers ([rows, D] of o_dtype_in, fp32 [rows]);
+ * 1 <= n <= HG_MAX_PARTS.  LSE_out may be NULL.  O_out may alias O_parts[0] when the dtypes are equal.
+ */
+int hg_merge(hg_ctx* ctx, int n, const void* const* O_parts, const float* const* LSE_parts, int o_dtype_in,
+             int64_t rows, int D, void* O_out, int o_dtype_out, float* LSE_out);
+
+/*
+ * Fused Hydragen attention (App. B's top-level routine, generalised to n_levels >= 0 levels of shared
+ * blocks): one batched attention per level, the suffix attention, and the merge of all partial results.
+ * The suffix may be absent (Ks == NULL: lengths are then taken as 0).
+ * O_out : [B, Hq, D] of o_dtype;  LSE_out : fp32 [B, Hq] or NULL.
+ */
+int hg_hydragen_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* levels,
+                     const void* Ks, const void* Vs, const int32_t* offsets, const int32_t* lengths, int max_len,
+                     int B, int Hq, int Hkv, int D, float scale,
+                     void* O_out, int o_dtype, float* LSE_out);
+
+/*
+ * Non-decomposed comparison (the behaviour Sec. 1 and Sec. 2.3 attribute to per-sequence decode kernels):
+ * same arguments and result as hg_hydragen_attn, but every sequence walks its whole key list
+ * (shared blocks, then suffix) by itself, so shared rows are re-read once per sequence.
+ */
+int hg_naive_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* levels,
+                  const void* Ks, const void* Vs, const int32_t* offsets, const int32_t* lengths, int max_len,
+                  int B, int Hq, int Hkv, int D, float scale,
+                  void* O_out, int o_dtype, float* LSE_out);
+
+const char* hg_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYDRAGEN_H */

@@ -1,0 +1,247 @@
+"""Thin ctypes binding of libhydragen.so: same names as include/hydragen.h, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the attention path runs in the HIP kernels of
+the shared library.  There is no fallback: if the library is missing or fails to load, importing the symbols
+works but the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+HG_OK, HG_ERR_INVALID_ARG, HG_ERR_UNSUPPORTED, HG_ERR_WORKSPACE, HG_ERR_HIP = 0, 1, 2, 3, 4
+HG_F32, HG_BF16 = 0, 1
+HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
+HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK = 1, 2, 3, 4
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhydragen.so")
+
+# every symbol include/hydragen.h declares
+EXPORTS = (
+    "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
+    "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_strerror",
+)
+
+
+class HydragenError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+class hg_level(ctypes.Structure):
+    _fields_ = [
+        ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("n_blocks", ctypes.c_int),
+        ("kv_off", ctypes.c_void_p), ("seq_off", ctypes.c_void_p),
+        ("max_rows", ctypes.c_int), ("max_seqs", ctypes.c_int),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libhydragen.so (built by paper_2402_05099_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2402_05099_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, cf, cs = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.hg_create.argtypes = [ctypes.POINTER(vp), ci, vp, vp, cs]
+        L.hg_create.restype = ci
+        L.hg_destroy.argtypes = [vp]
+        L.hg_destroy.restype = None
+        L.hg_set_stream.argtypes = [vp, vp]
+        L.hg_set_stream.restype = ci
+        L.hg_set_option.argtypes = [vp, ci, ci]
+        L.hg_set_option.restype = ci
+        L.hg_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        L.hg_workspace_bytes.restype = cs
+        L.hg_prefix_attn.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_prefix_attn.restype = ci
+        L.hg_prefix_attn_grouped.argtypes = [vp, vp, ctypes.POINTER(hg_level), ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_prefix_attn_grouped.restype = ci
+        L.hg_suffix_attn.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_suffix_attn.restype = ci
+        L.hg_merge.argtypes = [vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, ctypes.c_int64, ci, vp, ci, vp]
+        L.hg_merge.restype = ci
+        fused = [vp, vp, ci, ctypes.POINTER(hg_level), vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_hydragen_attn.argtypes = fused
+        L.hg_hydragen_attn.restype = ci
+        L.hg_naive_attn.argtypes = fused
+        L.hg_naive_attn.restype = ci
+        L.hg_strerror.argtypes = [ci]
+        L.hg_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().hg_strerror(int(code)).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != HG_OK:
+        raise HydragenError(code, what)
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return HG_F32
+    if t.dtype == torch.bfloat16:
+        return HG_BF16
+    raise TypeError(f"O must be float32 or bfloat16, got {t.dtype}")
+
+
+def _want(t: torch.Tensor, dtype, shape=None, name="tensor"):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError(f"{name}: need a contiguous device tensor of {dtype}, got {t.dtype} on {t.device}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != {tuple(shape)}")
+
+
+def hg_workspace_bytes(B: int, Hq: int, D: int, parts: int) -> int:
+    return int(lib().hg_workspace_bytes(B, Hq, D, parts))
+
+
+@dataclass
+class Level:
+    """One level of shared blocks on the device (see hg_level in include/hydragen.h)."""
+    K: torch.Tensor                      # bf16 [rows, Hkv, D]
+    V: torch.Tensor
+    n_blocks: int = 1
+    kv_off: Optional[torch.Tensor] = None   # int32 [n_blocks+1] on device, or None for one block covering all
+    seq_off: Optional[torch.Tensor] = None
+    max_rows: int = 0
+    max_seqs: int = 0
+
+    def c_struct(self) -> hg_level:
+        return hg_level(self.K.data_ptr(), self.V.data_ptr(), self.n_blocks,
+                        None if self.kv_off is None else self.kv_off.data_ptr(),
+                        None if self.seq_off is None else self.seq_off.data_ptr(),
+                        self.max_rows, self.max_seqs)
+
+
+class Context:
+    """Owns an hg_ctx and its workspace tensor (device memory comes from PyTorch)."""
+
+    def __init__(self, device: int = 0, workspace_bytes: int = 0, stream: Optional[torch.cuda.Stream] = None):
+        L = lib()
+        self.device = device
+        self.workspace = None
+        if workspace_bytes:
+            self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=f"cuda:{device}")
+        self._stream = stream
+        h = ctypes.c_void_p()
+        sp = ctypes.c_void_p(self._stream_handle(stream))
+        _check(L.hg_create(ctypes.byref(h), device, sp, _p(self.workspace), workspace_bytes), "hg_create")
+        self.h = h
+
+    def _stream_handle(self, stream) -> int:
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        return int(stream.cuda_stream)
+
+    def set_stream(self, stream: Optional[torch.cuda.Stream]) -> None:
+        self._stream = stream
+        _check(lib().hg_set_stream(self.h, ctypes.c_void_p(self._stream_handle(stream))), "hg_set_stream")
+
+    def set_option(self, option: int, value: int) -> None:
+        _check(lib().hg_set_option(self.h, option, value), "hg_set_option")
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            lib().hg_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def hg_prefix_attn(ctx: Context, Q, Kp, Vp, O, LSE, scale: float = 0.0) -> None:
+    B, Hq, D = Q.shape
+    P, Hkv, _ = Kp.shape
+    _want(Q, torch.bfloat16, name="Q"); _want(Kp, torch.bfloat16, (P, Hkv, D), "Kp"); _want(Vp, torch.bfloat16, (P, Hkv, D), "Vp")
+    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    _check(lib().hg_prefix_attn(ctx.h, _p(Q), _p(Kp), _p(Vp), B, Hq, Hkv, D, P, scale, _p(O), _dtype_code(O), _p(LSE)),
+           "hg_prefix_attn")
+
+
+def hg_prefix_attn_grouped(ctx: Context, Q, level: Level, O, LSE, scale: float = 0.0) -> None:
+    B, Hq, D = Q.shape
+    Hkv = level.K.shape[1]
+    _want(Q, torch.bfloat16, name="Q"); _want(level.K, torch.bfloat16, name="K"); _want(level.V, torch.bfloat16, level.K.shape, "V")
+    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    st = level.c_struct()
+    _check(lib().hg_prefix_attn_grouped(ctx.h, _p(Q), ctypes.byref(st), B, Hq, Hkv, D, scale, _p(O), _dtype_code(O), _p(LSE)),
+           "hg_prefix_attn_grouped")
+
+
+def hg_suffix_attn(ctx: Context, Q, Ks, Vs, offsets, lengths, max_len: int, O, LSE, scale: float = 0.0) -> None:
+    B, Hq, D = Q.shape
+    Hkv = Ks.shape[1]
+    _want(Q, torch.bfloat16, name="Q"); _want(Ks, torch.bfloat16, name="Ks"); _want(Vs, torch.bfloat16, Ks.shape, "Vs")
+    _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    _check(lib().hg_suffix_attn(ctx.h, _p(Q), _p(Ks), _p(Vs), _p(offsets), _p(lengths), max_len, B, Hq, Hkv, D, scale,
+                                _p(O), _dtype_code(O), _p(LSE)), "hg_suffix_attn")
+
+
+def hg_merge(ctx: Context, O_parts: Sequence[torch.Tensor], LSE_parts: Sequence[torch.Tensor], O_out, LSE_out=None) -> None:
+    n = len(O_parts)
+    D = O_parts[0].shape[-1]
+    rows = O_parts[0].numel() // D
+    for o, l in zip(O_parts, LSE_parts):
+        _want(o, O_parts[0].dtype, O_parts[0].shape, "O_part"); _want(l, torch.float32, O_parts[0].shape[:-1], "LSE_part")
+    _want(O_out, O_out.dtype, O_parts[0].shape, "O_out")
+    if LSE_out is not None:
+        _want(LSE_out, torch.float32, O_parts[0].shape[:-1], "LSE_out")
+    op = (ctypes.c_void_p * n)(*[o.data_ptr() for o in O_parts])
+    lp = (ctypes.c_void_p * n)(*[l.data_ptr() for l in LSE_parts])
+    _check(lib().hg_merge(ctx.h, n, op, lp, _dtype_code(O_parts[0]), rows, D, _p(O_out), _dtype_code(O_out), _p(LSE_out)),
+           "hg_merge")
+
+
+def _fused(fn, name, ctx, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale):
+    B, Hq, D = Q.shape
+    _want(Q, torch.bfloat16, name="Q")
+    if levels:
+        Hkv = levels[0].K.shape[1]
+    elif Ks is not None:
+        Hkv = Ks.shape[1]
+    else:
+        raise ValueError("no keys at all")
+    for lv in levels:
+        _want(lv.K, torch.bfloat16, name="level K"); _want(lv.V, torch.bfloat16, lv.K.shape, "level V")
+    if Ks is not None:
+        _want(Ks, torch.bfloat16, name="Ks"); _want(Vs, torch.bfloat16, Ks.shape, "Vs")
+        _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _want(O_out, O_out.dtype, (B, Hq, D), "O_out")
+    if LSE_out is not None:
+        _want(LSE_out, torch.float32, (B, Hq), "LSE_out")
+    n = len(levels)
+    arr = (hg_level * max(n, 1))(*[lv.c_struct() for lv in levels])
+    _check(fn(ctx.h, _p(Q), n, arr, _p(Ks), _p(Vs), _p(offsets), _p(lengths), max_len, B, Hq, Hkv, D, scale,
+              _p(O_out), _dtype_code(O_out), _p(LSE_out)), name)
+
+
+def hg_hydragen_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,
+                     scale: float = 0.0) -> None:
+    _fused(lib().hg_hydragen_attn, "hg_hydragen_attn", ctx, Q, levels, Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale)
+
+
+def hg_naive_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,
+                  scale: float = 0.0) -> None:
+    _fused(lib().hg_naive_attn, "hg_naive_attn", ctx, Q, levels, Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale)

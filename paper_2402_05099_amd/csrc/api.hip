@@ -1,0 +1,490 @@
+// Host side of libhydragen: argument checks, work partitioning, kernel sequencing.  No device allocation,
+// no host synchronisation, no copies: every entry point only enqueues kernels on the context's stream.
+#include <math.h>
+#include <new>
+
+#include "hg_internal.h"
+
+struct hg_ctx {
+    int device;
+    hipStream_t stream;
+    unsigned char* ws;
+    size_t ws_bytes;
+    int opt_prefix_splits;
+    int opt_suffix_chunk;
+    int opt_overlap;
+    int opt_naive_chunk;
+    hipStream_t aux;       // second stream for the overlap option
+    hipEvent_t ev_fork, ev_join;
+};
+
+namespace {
+
+using namespace hg;
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+struct Parts {   // fp32 partial results carved out of the workspace
+    float* O;    // [cap][rows][D]
+    float* L;    // [cap][rows]
+    int cap;
+    int64_t rows;
+    int D;
+    float* o(int p) const { return O + (int64_t)p * rows * D; }
+    float* l(int p) const { return L + (int64_t)p * rows; }
+};
+
+Parts carve(const hg_ctx* c, int64_t rows, int D) {
+    Parts p{};
+    p.rows = rows;
+    p.D = D;
+    const size_t per = (size_t)rows * (D + 1) * sizeof(float);
+    size_t cap = (c->ws && per) ? c->ws_bytes / per : 0;
+    if (cap > HG_MAX_PARTS) cap = HG_MAX_PARTS;
+    p.cap = (int)cap;
+    p.O = reinterpret_cast<float*>(c->ws);
+    p.L = p.O + (int64_t)p.cap * rows * D;
+    return p;
+}
+
+int check_shape(int B, int Hq, int Hkv, int D) {
+    if (B < 0 || Hq <= 0 || Hkv <= 0) return HG_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return HG_ERR_UNSUPPORTED;
+    if (Hq % Hkv != 0) return HG_ERR_UNSUPPORTED;
+    if ((int64_t)B * Hq * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    return HG_OK;
+}
+
+int check_level(const hg_level* lv, int Hkv, int D) {
+    if (!lv) return HG_ERR_INVALID_ARG;
+    if (lv->n_blocks < 1 || lv->max_rows < 0 || lv->max_seqs < 0) return HG_ERR_INVALID_ARG;
+    if ((lv->kv_off == nullptr) != (lv->seq_off == nullptr)) return HG_ERR_INVALID_ARG;
+    if (lv->n_blocks > 1 && !lv->kv_off) return HG_ERR_INVALID_ARG;
+    if (lv->max_rows > 0 && (!lv->K || !lv->V)) return HG_ERR_INVALID_ARG;
+    if ((int64_t)lv->n_blocks * lv->max_rows * Hkv * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    return HG_OK;
+}
+
+LevelDev to_dev(const hg_level& lv, int B) {
+    LevelDev d{};
+    d.K = static_cast<const uint16_t*>(lv.K);
+    d.V = static_cast<const uint16_t*>(lv.V);
+    d.kv_off = lv.kv_off;
+    d.seq_off = lv.seq_off;
+    d.n_blocks = lv.n_blocks;
+    d.max_rows = lv.max_rows;
+    d.max_seqs = lv.kv_off ? lv.max_seqs : B;
+    return d;
+}
+
+int pick_gt(int G) {
+    for (int gt : {8, 4, 2}) if (G % gt == 0) return gt;
+    return 1;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
+
+// default number of key-range splits for one level
+int default_splits(const hg_ctx* c, const LevelDev& lv, int Hkv, int G) {
+    if (lv.max_rows <= 0) return 1;
+    int ns;
+    if (c->opt_prefix_splits > 0) {
+        ns = c->opt_prefix_splits;
+    } else {
+        const int64_t base = (int64_t)lv.n_blocks * ceil_div(lv.max_seqs * G, kPrefixRows) * Hkv;
+        ns = (int)((1536 + base - 1) / (base > 0 ? base : 1));
+        const int by_len = lv.max_rows / 256;
+        if (ns > by_len) ns = by_len;
+        if (ns > 16) ns = 16;
+    }
+    const int max_ns = ceil_div(lv.max_rows, kPrefixKeys);
+    if (ns > max_ns) ns = max_ns;
+    if (ns < 1) ns = 1;
+    return ns;
+}
+
+// enqueue the shared-block kernel for one level with `ns` splits writing to `out` (part = split)
+int run_level(const hg_ctx* c, const void* Q, const LevelDev& lv, int ns, int B, int Hq, int Hkv, int D, float scale,
+              const OutDev& out, hipStream_t s) {
+    PrefixArgs a{};
+    a.Q = static_cast<const uint16_t*>(Q);
+    a.lv = lv;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
+    a.mtiles = ceil_div(lv.max_seqs * a.G, kPrefixRows);
+    a.nsplit = ns;
+    a.chunk = round_up(ceil_div(lv.max_rows > 0 ? lv.max_rows : 1, ns), kPrefixKeys);
+    const int64_t total = (int64_t)lv.n_blocks * ns * Hkv * a.mtiles;
+    if (total >= (1LL << 28)) return HG_ERR_UNSUPPORTED;
+    a.total_tiles = (int)total;
+    a.per_xcd = ceil_div(a.total_tiles, 8);
+    a.scale = scale;
+    a.out = out;
+    (void)c;
+    return hip_rc(launch_prefix(a, D, s));
+}
+
+struct SuffixPlan { int chunk, nchunks, gt; };
+
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G) {
+    SuffixPlan p;
+    p.gt = pick_gt(G);
+    p.chunk = c->opt_suffix_chunk > 0 ? round_up(c->opt_suffix_chunk, 32) : 256;
+    p.nchunks = max_len > 0 ? ceil_div(max_len, p.chunk) : 1;
+    return p;
+}
+
+int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
+               const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
+               int gt, const OutDev& out, hipStream_t s) {
+    DecodeArgs a{};
+    a.Q = static_cast<const uint16_t*>(Q);
+    a.n_levels = n_levels;
+    for (int i = 0; i < n_levels; ++i) a.lv[i] = lv[i];
+    a.Ks = static_cast<const uint16_t*>(Ks);
+    a.Vs = static_cast<const uint16_t*>(Vs);
+    a.offsets = offsets;
+    a.lengths = lengths;
+    a.max_len = max_len;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
+    a.chunk = chunk;
+    a.nchunks = nchunks;
+    a.units = (int64_t)B * nchunks * Hkv * (a.G / gt);
+    a.scale = scale;
+    a.out = out;
+    return hip_rc(launch_decode(a, D, gt, s));
+}
+
+int run_merge(int n, const Parts& parts, int first, int D, void* O_out, int o_dtype, float* LSE_out, hipStream_t s) {
+    MergeArgs m{};
+    m.n = n;
+    for (int i = 0; i < n; ++i) {
+        m.O[i] = parts.o(first + i);
+        m.L[i] = parts.l(first + i);
+    }
+    m.rows = parts.rows;
+    m.O_out = O_out;
+    m.L_out = LSE_out;
+    return hip_rc(launch_merge(m, D, false, o_dtype == HG_BF16, s));
+}
+
+float eff_scale(float scale, int D) { return scale > 0.f ? scale : 1.0f / sqrtf((float)D); }
+
+OutDev direct_out(void* O, int o_dtype, float* LSE) {
+    OutDev o{};
+    o.O = O; o.LSE = LSE; o.bf16 = (o_dtype == HG_BF16); o.part_stride_O = 0; o.part_stride_L = 0;
+    return o;
+}
+
+OutDev parts_out(const Parts& p, int first) {
+    OutDev o{};
+    o.O = p.o(first); o.LSE = p.l(first); o.bf16 = 0;
+    o.part_stride_O = p.rows * p.D; o.part_stride_L = p.rows;
+    return o;
+}
+
+int fill_empty(void* O, int o_dtype, float* LSE, int64_t rows, int D, hipStream_t s) {
+    FillArgs f{};
+    f.O = O; f.LSE = LSE; f.bf16 = (o_dtype == HG_BF16); f.rows = rows; f.D = D;
+    return hip_rc(launch_fill_empty(f, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_t workspace_bytes) {
+    if (!out) return HG_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (workspace_bytes && !workspace) return HG_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return HG_ERR_INVALID_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return HG_ERR_HIP;
+    if (hipSetDevice(device) != hipSuccess) return HG_ERR_HIP;
+    hg_ctx* c = new (std::nothrow) hg_ctx();
+    if (!c) return HG_ERR_HIP;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->ws = static_cast<unsigned char*>(workspace);
+    c->ws_bytes = workspace_bytes;
+    c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = 0;
+    c->aux = nullptr;
+    c->ev_fork = c->ev_join = nullptr;
+    if (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        hg_destroy(c);
+        return HG_ERR_HIP;
+    }
+    *out = c;
+    return HG_OK;
+}
+
+void hg_destroy(hg_ctx* c) {
+    if (!c) return;
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->aux) (void)hipStreamDestroy(c->aux);
+    delete c;
+}
+
+int hg_set_stream(hg_ctx* c, void* hip_stream) {
+    if (!c) return HG_ERR_INVALID_ARG;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    return HG_OK;
+}
+
+int hg_set_option(hg_ctx* c, int option, int value) {
+    if (!c || value < 0) return HG_ERR_INVALID_ARG;
+    switch (option) {
+        case HG_OPT_PREFIX_SPLITS: c->opt_prefix_splits = value; return HG_OK;
+        case HG_OPT_SUFFIX_CHUNK: c->opt_suffix_chunk = value; return HG_OK;
+        case HG_OPT_OVERLAP: c->opt_overlap = value; return HG_OK;
+        case HG_OPT_NAIVE_CHUNK: c->opt_naive_chunk = value; return HG_OK;
+    }
+    return HG_ERR_INVALID_ARG;
+}
+
+size_t hg_workspace_bytes(int B, int Hq, int D, int parts) {
+    if (B <= 0 || Hq <= 0 || D <= 0 || parts <= 0) return 0;
+    const size_t n = (size_t)parts * (size_t)B * Hq * (size_t)(D + 1) * sizeof(float);
+    return (n + 255) / 256 * 256;
+}
+
+int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int B, int Hq, int Hkv, int D, float scale,
+                           void* O, int o_dtype, float* LSE) {
+    if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16)) return HG_ERR_INVALID_ARG;
+    int rc = check_shape(B, Hq, Hkv, D);
+    if (rc) return rc;
+    rc = check_level(level, Hkv, D);
+    if (rc) return rc;
+    if (B == 0) return HG_OK;
+    if (!Q) return HG_ERR_INVALID_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    scale = eff_scale(scale, D);
+    const int64_t rows = (int64_t)B * Hq;
+    const LevelDev lv = to_dev(*level, B);
+    const Parts parts = carve(c, rows, D);
+    int ns = default_splits(c, lv, Hkv, Hq / Hkv);
+    if (ns > parts.cap) ns = parts.cap > 1 ? parts.cap : 1;
+    hipStream_t s = c->stream;
+    if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
+    if (ns == 1) {
+        if (lv.seq_off) {
+            rc = fill_empty(O, o_dtype, LSE, rows, D, s);
+            if (rc) return rc;
+        }
+        return run_level(c, Q, lv, 1, B, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
+    }
+    if (lv.seq_off) {
+        rc = fill_empty(nullptr, HG_F32, parts.l(0), rows * ns, D, s);
+        if (rc) return rc;
+    }
+    rc = run_level(c, Q, lv, ns, B, Hq, Hkv, D, scale, parts_out(parts, 0), s);
+    if (rc) return rc;
+    return run_merge(ns, parts, 0, D, O, o_dtype, LSE, s);
+}
+
+int hg_prefix_attn(hg_ctx* c, const void* Q, const void* Kp, const void* Vp, int B, int Hq, int Hkv, int D, int P,
+                   float scale, void* O, int o_dtype, float* LSE) {
+    if (P < 0) return HG_ERR_INVALID_ARG;
+    hg_level lv{};
+    lv.K = Kp; lv.V = Vp; lv.n_blocks = 1; lv.kv_off = nullptr; lv.seq_off = nullptr; lv.max_rows = P; lv.max_seqs = B;
+    return hg_prefix_attn_grouped(c, Q, &lv, B, Hq, Hkv, D, scale, O, o_dtype, LSE);
+}
+
+int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, const int32_t* offsets,
+                   const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
+                   float* LSE) {
+    if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
+    int rc = check_shape(B, Hq, Hkv, D);
+    if (rc) return rc;
+    if (B == 0) return HG_OK;
+    if (!Q || !offsets || !lengths) return HG_ERR_INVALID_ARG;
+    if (max_len > 0 && (!Ks || !Vs)) return HG_ERR_INVALID_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    scale = eff_scale(scale, D);
+    const int64_t rows = (int64_t)B * Hq;
+    hipStream_t s = c->stream;
+    if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
+    const Parts parts = carve(c, rows, D);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv);
+    if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
+        p.nchunks = parts.cap > 1 ? parts.cap : 1;
+        p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
+        p.nchunks = ceil_div(max_len, p.chunk);
+    }
+    if (p.nchunks == 1)
+        return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
+                          direct_out(O, o_dtype, LSE), s);
+    rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
+                    parts_out(parts, 0), s);
+    if (rc) return rc;
+    return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
+}
+
+int hg_merge(hg_ctx* c, int n, const void* const* O_parts, const float* const* LSE_parts, int o_dtype_in, int64_t rows,
+             int D, void* O_out, int o_dtype_out, float* LSE_out) {
+    if (!c || n < 1 || n > HG_MAX_PARTS || !O_parts || !LSE_parts || rows < 0 || !O_out) return HG_ERR_INVALID_ARG;
+    if ((o_dtype_in != HG_F32 && o_dtype_in != HG_BF16) || (o_dtype_out != HG_F32 && o_dtype_out != HG_BF16))
+        return HG_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return HG_ERR_UNSUPPORTED;
+    for (int i = 0; i < n; ++i)
+        if (!O_parts[i] || !LSE_parts[i]) return HG_ERR_INVALID_ARG;
+    if (rows == 0) return HG_OK;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    hg::MergeArgs m{};
+    m.n = n;
+    for (int i = 0; i < n; ++i) {
+        m.O[i] = O_parts[i];
+        m.L[i] = LSE_parts[i];
+    }
+    m.rows = rows;
+    m.O_out = O_out;
+    m.L_out = LSE_out;
+    return hip_rc(hg::launch_merge(m, D, o_dtype_in == HG_BF16, o_dtype_out == HG_BF16, c->stream));
+}
+
+static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                       const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
+                       void* O_out, int o_dtype) {
+    if (!c || !O_out || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
+    if (n_levels < 0 || n_levels > HG_MAX_LEVELS || (n_levels > 0 && !levels)) return HG_ERR_INVALID_ARG;
+    int rc = check_shape(B, Hq, Hkv, D);
+    if (rc) return rc;
+    for (int i = 0; i < n_levels; ++i) {
+        rc = check_level(&levels[i], Hkv, D);
+        if (rc) return rc;
+    }
+    if (B > 0 && !Q) return HG_ERR_INVALID_ARG;
+    if (Ks && max_len > 0 && (!Vs || !offsets || !lengths)) return HG_ERR_INVALID_ARG;
+    return HG_OK;
+}
+
+int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                     const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
+                     float scale, void* O_out, int o_dtype, float* LSE_out) {
+    int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype);
+    if (rc) return rc;
+    if (B == 0) return HG_OK;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    scale = eff_scale(scale, D);
+    const int64_t rows = (int64_t)B * Hq;
+    const int G = Hq / Hkv;
+    const bool has_suffix = Ks != nullptr && max_len > 0;
+    const Parts parts = carve(c, rows, D);
+
+    // plan: parts per level and for the suffix, shrunk to fit the workspace
+    LevelDev lv[HG_MAX_LEVELS];
+    int ns[HG_MAX_LEVELS];
+    int nlev = 0;
+    for (int i = 0; i < n_levels; ++i) {
+        LevelDev d = to_dev(levels[i], B);
+        if (d.max_rows == 0 || d.max_seqs == 0) continue;  // empty level contributes nothing
+        lv[nlev] = d;
+        ns[nlev] = default_splits(c, d, Hkv, G);
+        ++nlev;
+    }
+    SuffixPlan sp = plan_suffix(c, max_len, G);
+    if (!has_suffix) sp.nchunks = 0;
+    auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
+    if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
+    while (total_parts() > parts.cap) {  // shrink the largest split count first
+        int big = -1, bigv = 1;
+        for (int i = 0; i < nlev; ++i) if (ns[i] > bigv) { bigv = ns[i]; big = i; }
+        if (sp.nchunks > bigv) {
+            sp.nchunks -= 1;
+            sp.chunk = round_up(ceil_div(max_len, sp.nchunks), 32);
+            sp.nchunks = ceil_div(max_len, sp.chunk);
+        } else if (big >= 0) {
+            ns[big] -= 1;
+        } else {
+            return HG_ERR_WORKSPACE;
+        }
+    }
+    const int np = total_parts();
+    hipStream_t s = c->stream;
+    if (np == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
+
+    // grouped levels may leave sequences uncovered: their partial LSE must read -inf
+    int first = 0;
+    for (int i = 0; i < nlev; ++i) {
+        if (lv[i].seq_off) {
+            rc = fill_empty(nullptr, HG_F32, parts.l(first), rows * ns[i], D, s);
+            if (rc) return rc;
+        }
+        first += ns[i];
+    }
+
+    const bool overlap = c->opt_overlap && has_suffix && nlev > 0;
+    hipStream_t ssfx = s;
+    if (overlap) {
+        if (hipEventRecord(c->ev_fork, s) != hipSuccess) return HG_ERR_HIP;
+        if (hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess) return HG_ERR_HIP;
+        ssfx = c->aux;
+    }
+    first = 0;
+    for (int i = 0; i < nlev; ++i) first += ns[i];
+    if (has_suffix) {
+        rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, sp.chunk, sp.nchunks,
+                        sp.gt, parts_out(parts, first), ssfx);
+        if (rc) return rc;
+        if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
+    }
+    first = 0;
+    for (int i = 0; i < nlev; ++i) {
+        rc = run_level(c, Q, lv[i], ns[i], B, Hq, Hkv, D, scale, parts_out(parts, first), s);
+        if (rc) return rc;
+        first += ns[i];
+    }
+    if (overlap && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HG_ERR_HIP;
+    return run_merge(np, parts, 0, D, O_out, o_dtype, LSE_out, s);
+}
+
+int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                  const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale,
+                  void* O_out, int o_dtype, float* LSE_out) {
+    int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype);
+    if (rc) return rc;
+    if (B == 0) return HG_OK;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    scale = eff_scale(scale, D);
+    const int64_t rows = (int64_t)B * Hq;
+    const int G = Hq / Hkv;
+    const bool has_suffix = Ks != nullptr && max_len > 0;
+    const Parts parts = carve(c, rows, D);
+    LevelDev lv[HG_MAX_LEVELS];
+    int64_t nmax = has_suffix ? max_len : 0;
+    for (int i = 0; i < n_levels; ++i) {
+        lv[i] = to_dev(levels[i], B);
+        nmax += lv[i].max_rows;
+    }
+    hipStream_t s = c->stream;
+    if (parts.cap < 1) return HG_ERR_WORKSPACE;
+    if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
+    if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
+    int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 512;
+    int nchunks = ceil_div((int)nmax, chunk);
+    const int cap = parts.cap < 32 ? parts.cap : 32;
+    if (nchunks > cap) {
+        chunk = round_up(ceil_div((int)nmax, cap), 32);
+        nchunks = ceil_div((int)nmax, chunk);
+    }
+    rc = run_decode(Q, n_levels, lv, has_suffix ? Ks : nullptr, Vs, offsets, has_suffix ? lengths : nullptr, max_len, B, Hq,
+                    Hkv, D, scale, chunk, nchunks, pick_gt(G), parts_out(parts, 0), s);
+    if (rc) return rc;
+    return run_merge(nchunks, parts, 0, D, O_out, o_dtype, LSE_out, s);
+}
+
+const char* hg_strerror(int code) {
+    switch (code) {
+        case HG_OK: return "ok";
+        case HG_ERR_INVALID_ARG: return "invalid argument";
+        case HG_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case HG_ERR_WORKSPACE: return "workspace too small";
+        case HG_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown error";
+}
+
+}  // extern "C"

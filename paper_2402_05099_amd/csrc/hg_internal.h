@@ -1,0 +1,103 @@
+// Internal declarations shared by the HIP translation units of libhydragen (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hydragen.h"
+
+namespace hg {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- device-side descriptions --------------------------------------------------------------------
+
+struct LevelDev {
+    const uint16_t* K;
+    const uint16_t* V;
+    const int32_t* kv_off;   // may be null when n_blocks == 1
+    const int32_t* seq_off;  // may be null when n_blocks == 1
+    int n_blocks;
+    int max_rows;
+    int max_seqs;
+};
+
+// Where a kernel puts a partial (or final) result for query row idx = b*Hq + h.
+struct OutDev {
+    void* O;          // [rows, D] fp32 or bf16
+    float* LSE;       // [rows]
+    int bf16;         // 1: O is bf16
+    int64_t part_stride_O;    // elements between consecutive parts (0 when a single part)
+    int64_t part_stride_L;
+};
+
+struct PrefixArgs {
+    const uint16_t* Q;
+    LevelDev lv;
+    int B, Hq, Hkv, G;
+    int mtiles;       // query-row tiles per (block, KV head)
+    int nsplit;       // key-range splits per block
+    int chunk;        // keys per split (multiple of the key tile)
+    int total_tiles;  // n_blocks * nsplit * Hkv * mtiles
+    int per_xcd;      // ceil(total_tiles / 8)
+    float scale;      // softmax scale
+    OutDev out;       // part index = split
+};
+
+struct DecodeArgs {
+    const uint16_t* Q;
+    int n_levels;
+    LevelDev lv[HG_MAX_LEVELS];
+    const uint16_t* Ks;
+    const uint16_t* Vs;
+    const int32_t* offsets;
+    const int32_t* lengths;   // null: no suffix
+    int max_len;
+    int B, Hq, Hkv, G;
+    int chunk;        // keys per work item
+    int nchunks;      // work items per (sequence, KV head, query-head group)
+    int64_t units;    // B * nchunks * Hkv * (G / GT)
+    float scale;
+    OutDev out;       // part index = chunk
+};
+
+struct MergeArgs {
+    const void* O[HG_MAX_PARTS];
+    const float* L[HG_MAX_PARTS];
+    int n;
+    int64_t rows;
+    void* O_out;
+    float* L_out;     // may be null
+};
+
+struct FillArgs {
+    void* O; float* LSE; int bf16; int64_t rows; int D;
+};
+
+// ---- launchers (defined next to their kernels) ------------------------------------------------------
+hipError_t launch_prefix(const PrefixArgs& a, int D, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
+hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
+hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
+
+constexpr int kPrefixRows = 128;  // query rows per prefix workgroup
+constexpr int kPrefixKeys = 64;   // keys per prefix LDS tile
+
+// ---- small device helpers -------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+#endif
+
+}  // namespace hg

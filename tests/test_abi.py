@@ -1,0 +1,51 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and its pure host
+functions behave.  No kernel is launched here."""
+import os
+import re
+
+import pytest
+
+from paper_2402_05099_amd import binding as hb
+from paper_2402_05099_amd import build as hbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hb.LIB_PATH):
+        hbuild.build(verbose=False)
+    return hb.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hg_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_functions() == sorted(hb.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_workspace_bytes_and_strerror(lib):
+    assert hb.hg_workspace_bytes(1024, 40, 128, 3) == (3 * 1024 * 40 * 129 * 4 + 255) // 256 * 256
+    assert hb.hg_workspace_bytes(0, 40, 128, 3) == 0
+    assert hb.strerror(hb.HG_OK) == "ok"
+    assert hb.strerror(hb.HG_ERR_UNSUPPORTED) == "unsupported shape or dtype"
+    assert hb.strerror(12345) == "unknown error"
+
+
+def test_constants_match_header():
+    text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
+    for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_F32", "HG_BF16",
+                 "HG_MAX_LEVELS", "HG_MAX_PARTS", "HG_OPT_PREFIX_SPLITS", "HG_OPT_SUFFIX_CHUNK", "HG_OPT_OVERLAP",
+                 "HG_OPT_NAIVE_CHUNK"):
+        m = re.search(rf"\b{name}\s*=\s*(\d+)", text)
+        assert m, name
+        assert int(m.group(1)) == getattr(hb, name), name

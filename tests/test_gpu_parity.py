@@ -1,0 +1,285 @@
+"""GPU parity: every entry point of the C ABI against the fp64 CPU oracle on identical seeded inputs."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_05099_amd import binding as hb
+from paper_2402_05099_amd import device as dev
+from paper_2402_05099_amd import workloads as wl
+from parity import check, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def outputs(dw, dtype=torch.float32, canary=True):
+    """O/LSE buffers surrounded by NaN canaries so that out-of-range writes are seen."""
+    n = dw.rows * dw.D
+    pad = 256
+    fo = torch.full((n + 2 * pad,), float("nan"), dtype=dtype, device="cuda:0")
+    fl = torch.full((dw.rows + 2 * pad,), float("nan"), dtype=torch.float32, device="cuda:0")
+    O = fo[pad:pad + n].view(dw.B, dw.Hq, dw.D)
+    L = fl[pad:pad + dw.rows].view(dw.B, dw.Hq)
+
+    def intact():
+        torch.cuda.synchronize()
+        return bool(torch.isnan(fo[:pad]).all() and torch.isnan(fo[pad + n:]).all()
+                    and torch.isnan(fl[:pad]).all() and torch.isnan(fl[pad + dw.rows:]).all())
+    return O, L, intact
+
+
+WORKLOADS = {}
+
+
+def workload(key, **variant):
+    k = (key, tuple(sorted(variant.items())))
+    if k not in WORKLOADS:
+        w = wl.scaled_down(key, **variant) if isinstance(key, int) else key()
+        WORKLOADS[k] = (w, dev.to_device(w))
+    return WORKLOADS[k]
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("in_bf16,out_bf16", [(False, False), (False, True), (True, True), (True, False)])
+def test_merge(D, in_bf16, out_bf16):
+    say(f"merge D={D} in_bf16={in_bf16} out_bf16={out_bf16}")
+    rng = np.random.default_rng(11)
+    rows = 1000 + 37
+    ctx = hb.Context(0, 0)
+    for n in (1, 2, 3, 7):
+        Os = [wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(rng.standard_normal((rows, D)).astype(np.float32))) for _ in range(n)]
+        Ls = [(rng.standard_normal(rows) * 4).astype(np.float32) for _ in range(n)]
+        for i in range(n):  # sprinkle empty parts, and make row 5 empty everywhere
+            Ls[i][rng.integers(0, rows, 50)] = -np.inf
+            Ls[i][5] = -np.inf
+        Oref, Lref = oracle.merge(Os, Ls)
+        tin = torch.bfloat16 if in_bf16 else torch.float32
+        tO = [torch.from_numpy(o).cuda().to(tin) for o in Os]
+        tL = [torch.from_numpy(l).cuda() for l in Ls]
+        # uninitialised O of an empty part must never leak into the result
+        for i in range(n):
+            tO[i][torch.isneginf(tL[i])] = float("nan")
+        Oout = torch.full((rows, D), float("nan"), dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda:0")
+        Lout = torch.full((rows,), float("nan"), dtype=torch.float32, device="cuda:0")
+        hb.hg_merge(ctx, tO, tL, Oout, Lout)
+        torch.cuda.synchronize()
+        check(to_np(Oout), to_np(Lout), Oref, Lref, f"merge n={n}", out_bf16=out_bf16)
+        assert float(Oout[5].abs().max()) == 0.0
+    ctx.close()
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("chunk", [0, 32])
+def test_suffix_attn(idx, chunk):
+    say(f"suffix idx={idx} chunk={chunk}")
+    w, dw = workload(idx)
+    ctx = dev.make_context(dw, parts=8)
+    if chunk:
+        ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
+    Oref, Lref = oracle.attention(w, levels=[], suffix=True)
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"suffix idx={idx} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+@pytest.mark.parametrize("splits", [0, 1, 3])
+def test_prefix_attn(idx, splits):
+    say(f"prefix idx={idx} splits={splits}")
+    w, dw = workload(idx)
+    ctx = dev.make_context(dw, parts=8)
+    if splits:
+        ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    lv = dw.levels[0]
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"prefix idx={idx} splits={splits} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
+@pytest.mark.parametrize("splits", [0, 2])
+def test_prefix_attn_grouped_tree_levels(splits):
+    say(f"grouped splits={splits}")
+    w, dw = workload(5)
+    ctx = dev.make_context(dw, parts=8)
+    if splits:
+        ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
+    for li in (0, 1):
+        Oref, Lref = oracle.attention(w, levels=[li], suffix=False)
+        O, L, intact = outputs(dw)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[li], O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"grouped level {li}")
+    ctx.close()
+
+
+def test_grouped_level_with_uncovered_sequences_and_unequal_blocks():
+    say("grouped uncovered")
+    w = wl.make_workload("gaps", 21, 50, 8, 4, 128, [(3, 90, 11)], 5, 9)  # blocks cover sequences 0..32 only
+    lv = w.levels[0]
+    lv.kv_off = np.array([0, 90, 150, 270], np.int32)     # unequal rows: 90, 60, 120
+    lv.seq_off = np.array([0, 11, 30, 33], np.int32)      # unequal sequences: 11, 19, 3
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=8)
+    for splits in (1, 2):
+        ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
+        Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+        assert np.isneginf(Lref[40]).all()
+        O, L, intact = outputs(dw)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[0], O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"uncovered splits={splits}")
+        Of, Lf = oracle.attention(w)
+        O2, L2 = dev.hydragen(ctx, dw, torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(O2), to_np(L2), Of, Lf, "uncovered fused")
+        O3, L3 = dev.naive(ctx, dw, torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(O3), to_np(L3), Of, Lf, "uncovered naive")
+    ctx.close()
+
+
+VARIANTS = [dict(), dict(q_gain=4.0), dict(plant="suffix"), dict(plant="prefix")]
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", VARIANTS, ids=["normal", "peaked", "plant_suffix", "plant_prefix"])
+def test_fused_hydragen_and_naive(idx, variant):
+    say(f"fused idx={idx} {variant}")
+    w, dw = workload(idx, **variant)
+    ctx = dev.make_context(dw, parts=24)
+    Oref, Lref = oracle.attention(w)
+    for dtype in (torch.bfloat16, torch.float32):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert intact()
+        st = check(to_np(O), to_np(L), Oref, Lref, f"hydragen idx={idx} {variant} {dtype}", out_bf16=dtype == torch.bfloat16)
+        say(f"   hydragen {dtype}: {st}")
+    O, L, intact = outputs(dw, torch.float32)
+    hb.hg_naive_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+    assert intact()
+    check(to_np(O), to_np(L), Oref, Lref, f"naive idx={idx} {variant}")
+    # two-stream variant of the fused call gives the same bits
+    ctx.set_option(hb.HG_OPT_OVERLAP, 1)
+    O2, L2 = dev.hydragen(ctx, dw, torch.float32)
+    O1, L1 = outputs(dw, torch.float32)[:2]
+    ctx.set_option(hb.HG_OPT_OVERLAP, 0)
+    hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O1, L1, dw.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    ctx.close()
+
+
+def test_config1_exact_sizes_and_determinism():
+    say("config1")
+    w = wl.config(1)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw)
+    Oref, Lref = oracle.attention(w)
+    O, L = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, "config1")
+    O2, L2 = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(L, L2)
+    ctx.close()
+
+
+def test_edge_cases_empty_parts():
+    say("edge cases")
+    # P = 0 (standard attention), all-empty suffixes, some empty suffixes, B = 1, no suffix tensors at all
+    w = wl.make_workload("p0", 31, 9, 8, 4, 128, [(1, 0, 9)], 0, 40)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw)
+    Oref, Lref = oracle.attention(w)
+    O, L = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, "P=0")
+    Op, Lp, intact = outputs(dw)
+    hb.hg_prefix_attn(ctx, dw.Q, dw.levels[0].K, dw.levels[0].V, Op, Lp, dw.scale)
+    assert intact() and float(Op.abs().max()) == 0.0 and bool(torch.isneginf(Lp).all())
+    ctx.close()
+
+    w = wl.make_workload("l0", 32, 5, 4, 4, 64, [(1, 70, 5)], 0, 0)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw)
+    Oref, Lref = oracle.attention(w)
+    O, L = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, "L=0 everywhere")
+    Os, Ls, intact = outputs(dw)
+    hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, 0, Os, Ls, dw.scale)
+    assert intact() and bool(torch.isneginf(Ls).all())
+    # lengths given but Ks absent: treated as no suffix
+    O2 = torch.empty_like(O)
+    L2 = torch.empty_like(L)
+    hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, None, None, None, None, 0, O2, L2, dw.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+    ctx.close()
+
+    w = wl.make_workload("b1", 33, 1, 2, 1, 128, [(1, 65, 1)], 1, 1)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw)
+    Oref, Lref = oracle.attention(w)
+    O, L = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, "B=1")
+    ctx.close()
+
+
+def test_lengths_change_on_device_without_host_work():
+    """Suffix lengths live on the device: shrinking them between calls changes the result accordingly."""
+    say("device lengths")
+    w, dw = workload(2)
+    ctx = dev.make_context(dw)
+    new_len = np.maximum(w.lengths // 2, 0).astype(np.int32)
+    dw.lengths.copy_(torch.from_numpy(new_len))
+    w2 = wl.scaled_down(2)
+    w2.lengths = new_len
+    Oref, Lref = oracle.attention(w2)
+    O, L = dev.hydragen(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    dw.lengths.copy_(torch.from_numpy(w.lengths))
+    check(to_np(O), to_np(L), Oref, Lref, "halved lengths")
+    ctx.close()
+
+
+def test_error_paths_launch_nothing():
+    say("errors")
+    w, dw = workload(1)
+    ctx = dev.make_context(dw, parts=1)
+    O = torch.full((dw.B, dw.Hq, dw.D), 7.0, device="cuda:0")
+    L = torch.full((dw.B, dw.Hq), 7.0, device="cuda:0")
+    lib = hb.lib()
+    lv = dw.levels[0]
+    p = lambda t: t.data_ptr()
+    # unsupported head dim
+    assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 96, 128, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_UNSUPPORTED
+    # Hq not a multiple of Hkv
+    assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 3, 64, 128, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_UNSUPPORTED
+    # null output, negative length, bad dtype
+    assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 64, 128, 0.0, None, hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
+    assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 64, -1, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
+    assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 64, 128, 0.0, p(O), 9, p(L)) == hb.HG_ERR_INVALID_ARG
+    assert lib.hg_suffix_attn(ctx.h, p(dw.Q), p(dw.Ks), p(dw.Vs), p(dw.offsets), p(dw.lengths), -5, 4, 4, 4, 64, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
+    # fused call needs room for levels+1 partials: one part is not enough
+    with pytest.raises(hb.HydragenError) as e:
+        dev.hydragen(ctx, dw, torch.float32)
+    assert e.value.code == hb.HG_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert float(O.min()) == 7.0 and float(L.min()) == 7.0  # nothing was written
+    assert hb.strerror(hb.HG_ERR_WORKSPACE) == "workspace too small"
+    ctx.close()
