@@ -17,7 +17,8 @@
  * Conventions for every call
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
  *     never allocates or frees device memory after hg_create, never copies to
- *     or from the host, and never synchronises the host: work is enqueued on
+ *     or from the host, and never synchronises the host (hg_read_stage_timings, a
+ *     measurement aid, is the one exception): work is enqueued on
  *     the context's stream and the call returns.  Arrays of lengths/offsets are
  *     read on the device, so their values may change between calls without any
  *     host work.  Scalar shape arguments are host values.
@@ -59,8 +60,10 @@ enum {
     HG_OPT_PREFIX_SPLITS = 1, /* number of key-range splits of each shared block (>=1) */
     HG_OPT_SUFFIX_CHUNK = 2,  /* keys per work item of the suffix kernel (multiple of 32) */
     HG_OPT_OVERLAP = 3,       /* 1: run shared-block and suffix kernels on two streams inside the fused call */
-    HG_OPT_NAIVE_CHUNK = 4    /* keys per work item of the non-decomposed comparison kernel */
+    HG_OPT_NAIVE_CHUNK = 4,   /* keys per work item of the non-decomposed comparison kernel */
+    HG_OPT_STAGE_TIMING = 5   /* 1: hg_hydragen_attn brackets each of its kernels with timing events */
 };
+enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };
 
 /*
  * Create a context bound to `device`, enqueueing on `hip_stream` (a hipStream_t, NULL = default stream).
@@ -151,6 +154,19 @@ int hg_naive_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* leve
                   const void* Ks, const void* Vs, const int32_t* offsets, const int32_t* lengths, int max_len,
                   int B, int Hq, int Hkv, int D, float scale,
                   void* O_out, int o_dtype, float* LSE_out);
+
+/*
+ * Stage timings of the most recent fused calls (measurement aid; needs HG_OPT_STAGE_TIMING = 1 before them).
+ * Each hg_hydragen_attn call then records device-side timing events around its kernels, on the streams the
+ * kernels run on, into a ring of HG_TIMING_RING slots; nothing is synchronised at call time.
+ * hg_read_stage_timings waits for the newest recorded call to finish, then fills
+ *   ms[c * HG_MAX_STAGES + s] = milliseconds of stage s of the c-th most recent call, c = 0 .. n_calls-1
+ * (HOST array of n_calls * HG_MAX_STAGES floats), with stages: 0 = suffix kernel, 1 .. n_levels = the
+ * shared-block kernel of each non-empty level in order, n_levels + 1 = merge kernel; unused stages are 0.
+ * Returns the number of calls filled (<= n_calls, <= calls recorded since timing was enabled, <= ring size)
+ * or a negative error code.
+ */
+int hg_read_stage_timings(hg_ctx* ctx, float* ms, int n_calls);
 
 const char* hg_strerror(int code);
 

@@ -16,14 +16,16 @@ import torch
 HG_OK, HG_ERR_INVALID_ARG, HG_ERR_UNSUPPORTED, HG_ERR_WORKSPACE, HG_ERR_HIP = 0, 1, 2, 3, 4
 HG_F32, HG_BF16 = 0, 1
 HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
-HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK = 1, 2, 3, 4
+HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING = 1, 2, 3, 4, 5
+HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhydragen.so")
 
 # every symbol include/hydragen.h declares
 EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
-    "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_strerror",
+    "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
+    "hg_strerror",
 )
 
 
@@ -75,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.hg_hydragen_attn.restype = ci
         L.hg_naive_attn.argtypes = fused
         L.hg_naive_attn.restype = ci
+        L.hg_read_stage_timings.argtypes = [vp, ctypes.POINTER(cf), ci]
+        L.hg_read_stage_timings.restype = ci
         L.hg_strerror.argtypes = [ci]
         L.hg_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -157,6 +161,14 @@ class Context:
 
     def set_option(self, option: int, value: int) -> None:
         _check(lib().hg_set_option(self.h, option, value), "hg_set_option")
+
+    def read_stage_timings(self, n_calls: int):
+        """[[ms per stage] per call], newest call first (see hg_read_stage_timings)."""
+        buf = (ctypes.c_float * (n_calls * HG_MAX_STAGES))()
+        n = lib().hg_read_stage_timings(self.h, buf, n_calls)
+        if n < 0:
+            raise HydragenError(-n, "hg_read_stage_timings")
+        return [[buf[c * HG_MAX_STAGES + s] for s in range(HG_MAX_STAGES)] for c in range(n)]
 
     def close(self) -> None:
         if getattr(self, "h", None):

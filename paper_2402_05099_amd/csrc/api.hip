@@ -16,6 +16,11 @@ struct hg_ctx {
     int opt_naive_chunk;
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
+    // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
+    int opt_timing;
+    hipEvent_t* tev;       // [HG_TIMING_RING][HG_MAX_STAGES][2], created when timing is first enabled
+    unsigned char* tused;  // [HG_TIMING_RING][HG_MAX_STAGES]
+    long long tcalls;      // fused calls recorded since timing was enabled
 };
 
 namespace {
@@ -210,6 +215,10 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
+    c->opt_timing = 0;
+    c->tev = nullptr;
+    c->tused = nullptr;
+    c->tcalls = 0;
     if (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
@@ -225,6 +234,12 @@ void hg_destroy(hg_ctx* c) {
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->aux) (void)hipStreamDestroy(c->aux);
+    if (c->tev) {
+        for (int i = 0; i < HG_TIMING_RING * HG_MAX_STAGES * 2; ++i)
+            if (c->tev[i]) (void)hipEventDestroy(c->tev[i]);
+        delete[] c->tev;
+    }
+    delete[] c->tused;
     delete c;
 }
 
@@ -241,6 +256,19 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_SUFFIX_CHUNK: c->opt_suffix_chunk = value; return HG_OK;
         case HG_OPT_OVERLAP: c->opt_overlap = value; return HG_OK;
         case HG_OPT_NAIVE_CHUNK: c->opt_naive_chunk = value; return HG_OK;
+        case HG_OPT_STAGE_TIMING:
+            if (value && !c->tev) {
+                if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+                const int n = HG_TIMING_RING * HG_MAX_STAGES * 2;
+                c->tev = new (std::nothrow) hipEvent_t[n]();
+                c->tused = new (std::nothrow) unsigned char[HG_TIMING_RING * HG_MAX_STAGES]();
+                if (!c->tev || !c->tused) return HG_ERR_HIP;
+                for (int i = 0; i < n; ++i)
+                    if (hipEventCreate(&c->tev[i]) != hipSuccess) return HG_ERR_HIP;
+            }
+            c->opt_timing = value ? 1 : 0;
+            c->tcalls = 0;
+            return HG_OK;
     }
     return HG_ERR_INVALID_ARG;
 }
@@ -423,22 +451,40 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         if (hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess) return HG_ERR_HIP;
         ssfx = c->aux;
     }
+    // optional stage timing: events bracket each kernel on the stream it runs on
+    const int slot = c->opt_timing ? (int)(c->tcalls % HG_TIMING_RING) : -1;
+    if (slot >= 0)
+        for (int i = 0; i < HG_MAX_STAGES; ++i) c->tused[slot * HG_MAX_STAGES + i] = 0;
+    auto mark = [&](int stage, int which, hipStream_t st) -> bool {
+        if (slot < 0) return true;
+        c->tused[slot * HG_MAX_STAGES + stage] = 1;
+        return hipEventRecord(c->tev[(slot * HG_MAX_STAGES + stage) * 2 + which], st) == hipSuccess;
+    };
     first = 0;
     for (int i = 0; i < nlev; ++i) first += ns[i];
     if (has_suffix) {
+        if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
         rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, sp.chunk, sp.nchunks,
                         sp.gt, parts_out(parts, first), ssfx);
         if (rc) return rc;
+        if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
     }
     first = 0;
     for (int i = 0; i < nlev; ++i) {
+        if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
         rc = run_level(c, Q, lv[i], ns[i], B, Hq, Hkv, D, scale, parts_out(parts, first), s);
         if (rc) return rc;
+        if (!mark(1 + i, 1, s)) return HG_ERR_HIP;
         first += ns[i];
     }
     if (overlap && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HG_ERR_HIP;
-    return run_merge(np, parts, 0, D, O_out, o_dtype, LSE_out, s);
+    if (!mark(nlev + 1, 0, s)) return HG_ERR_HIP;
+    rc = run_merge(np, parts, 0, D, O_out, o_dtype, LSE_out, s);
+    if (rc) return rc;
+    if (!mark(nlev + 1, 1, s)) return HG_ERR_HIP;
+    if (slot >= 0) c->tcalls += 1;
+    return HG_OK;
 }
 
 int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
@@ -474,6 +520,27 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
                     Hkv, D, scale, chunk, nchunks, pick_gt(G), parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(nchunks, parts, 0, D, O_out, o_dtype, LSE_out, s);
+}
+
+int hg_read_stage_timings(hg_ctx* c, float* ms, int n_calls) {
+    if (!c || !ms || n_calls < 0) return -HG_ERR_INVALID_ARG;
+    if (!c->tev) return 0;
+    if (hipSetDevice(c->device) != hipSuccess) return -HG_ERR_HIP;
+    long long avail = c->tcalls < HG_TIMING_RING ? c->tcalls : HG_TIMING_RING;
+    const int n = (int)(n_calls < avail ? n_calls : avail);
+    for (int k = 0; k < n; ++k) {
+        const int slot = (int)((c->tcalls - 1 - k) % HG_TIMING_RING);
+        for (int st = 0; st < HG_MAX_STAGES; ++st) {
+            float t = 0.f;
+            if (c->tused[slot * HG_MAX_STAGES + st]) {
+                hipEvent_t e0 = c->tev[(slot * HG_MAX_STAGES + st) * 2], e1 = c->tev[(slot * HG_MAX_STAGES + st) * 2 + 1];
+                if (hipEventSynchronize(e1) != hipSuccess) return -HG_ERR_HIP;
+                if (hipEventElapsedTime(&t, e0, e1) != hipSuccess) return -HG_ERR_HIP;
+            }
+            ms[k * HG_MAX_STAGES + st] = t;
+        }
+    }
+    return n;
 }
 
 const char* hg_strerror(int code) {
