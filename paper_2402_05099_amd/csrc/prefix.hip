@@ -3,16 +3,21 @@
 // matrix cores, with an online softmax in registers, returning (O, LSE) (Eq. 1, Eq. 4).
 //
 // gfx950 design.  One workgroup = 4 wavefronts = 128 query rows (32 per wavefront) of one KV head and one
-// key-range split.  Keys stream through LDS in tiles of 64.  Everything is computed transposed so that a
-// lane owns ONE query column:
-//     S^T[key, q] = K_tile * Q^T        v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
-//     O^T[d, q]  += V^T_tile * P^T      A = V^T from LDS, B = P^T = the S^T accumulators, exponentiated
+// key-range split.  Keys stream through LDS in tiles of 64, double buffered; K and V tiles keep their HBM
+// layout [key][d] and are copied HBM -> LDS directly (global_load_lds_dwordx4, no register staging), with
+// the 16-byte chunks of each row XOR-swizzled so that both read patterns below are bank-conflict free.
+// Everything is computed transposed so that a lane owns ONE query column:
+//     S^T[key, q] = K_tile * Q^T        v_mfma_f32_32x32x16_bf16, A = K rows (ds_read_b128), B = Q (registers)
+//     O^T[d, q]  += V^T_tile * P^T      A = V^T via the transposing LDS read ds_read_b64_tr_b16, B = P^T
 // In the 32x32 accumulator layout lane l holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4 (r = 0..15),
 // so softmax statistics are per-lane scalars (one exchange with lane l^32 per tile), and the accumulators
-// of S^T are already in B-operand position for the second product once the key order inside each group of
-// 16 keys is relabelled (key 8a+4hl+b -> slot 8hl+4a+b); V^T is written to LDS in that relabelled order.
+// of S^T, exponentiated and packed to bf16, are already the B operand of the second product: k-slot j of
+// lane half hl in 16-key step t stands for key 16t + 8*(j/4) + 4*hl + j%4, and the V^T operand is read
+// in that same key order.
 // The softmax uses exp2 with scale*log2(e) folded into one FMA, and rescales O only when a row maximum
 // grows by more than 2^8 (the stale maximum cancels exactly in O = acc / l and LSE = m + log l).
+#include <type_traits>
+
 #include "hg_internal.h"
 
 namespace hg {
@@ -20,34 +25,48 @@ namespace hg {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
 
+#define HG_LDS(p) ((__attribute__((address_space(3))) unsigned char*)(p))
+#define HG_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// Value held by the lane 32 positions away.  v_permlane32_swap exchanges the upper 32 lanes of its first
+// operand with the lower 32 lanes of its second, so the partner's value arrives in the first result for
+// the upper half of the wavefront and in the second result for the lower half.
 __device__ __forceinline__ float other_half(float x) {
-    // value of the lane 32 positions away (v_permlane32_swap exchanges the upper half of the first operand
-    // with the lower half of the second)
     const unsigned u = __builtin_bit_cast(unsigned, x);
     auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
 }
+__device__ __forceinline__ float half_max(float x) { return fmaxf(x, other_half(x)); }
+__device__ __forceinline__ float half_sum(float x) { return x + other_half(x); }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     constexpr int KT = kPrefixKeys;        // 64 keys per tile
     constexpr int KS = D / 16;             // MFMA k-steps of the first product
     constexpr int DB = D / 32;             // 32-row blocks of O^T
-    constexpr int CPR = D / 8;             // 16-byte chunks per K row
-    constexpr int KCH = KT * CPR / 256;    // K chunks per thread per tile
-    constexpr int NK = D / 8;              // keys per thread when loading V (each thread owns 2 columns)
-    constexpr int KBYTES = KT * D * 2;
-    constexpr int VBYTES = D * KT * 2;
+    constexpr int CPR = D / 8;             // 16-byte chunks per K/V row
+    constexpr int RPI = 64 / CPR;          // rows one wavefront copies per direct-to-LDS instruction
+    constexpr int ROUNDS = KT / (4 * RPI); // such instructions per wavefront per tile and tensor
+    constexpr int ROWB = D * 2;            // bytes per row
+    constexpr int TILEB = KT * ROWB;       // bytes per K (or V) tile
+    constexpr int VM = CPR / 2;            // 32-byte chunk pairs per row (V swizzle works on pairs)
     constexpr float TAU = 8.0f;            // lazy-rescale threshold, log2 units
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // [K buf0][K buf1][V^T buf0][V^T buf1]
+    // Two K and two V tile buffers, each TILEB bytes, rows of ROWB bytes, chunk c of row r stored at chunk
+    // c ^ (r % CPR) for K and c ^ (2 * (r % VM)) for V.  They are four separate LDS objects on purpose: the
+    // compiler then knows that a copy in flight into one buffer does not alias reads of the other, and does
+    // not make those reads wait for the copy.
+    __shared__ __attribute__((aligned(1024))) unsigned char sK0[TILEB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sK1[TILEB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sV0[TILEB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sV1[TILEB];
 
     // ---- which tile -------------------------------------------------------------------------------
     const int pid = blockIdx.x;
-    const int slot = pid >> 3;
-    const int L = (pid & 7) * a.per_xcd + slot;  // consecutive logical tiles stay on one XCD (ids round-robin over 8 XCDs)
+    const int L = (pid & 7) * a.per_xcd + (pid >> 3);  // consecutive logical tiles stay on one XCD (ids round-robin over 8 XCDs)
     if (L >= a.total_tiles) return;
     int t = L;
     const int mt = t % a.mtiles; t /= a.mtiles;
@@ -69,7 +88,8 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     const int ke = min(ks + a.chunk, kv1);
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63, lq = l & 31, hl = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l = tid & 63, lq = l & 31, hl = l >> 5;
     const int r = row0 + w * 32 + lq;     // this lane's query row inside the block
     const bool rv = r < nrows;
     const int rr = rv ? r : 0;
@@ -104,68 +124,60 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         }
     }
 
-    // ---- global -> register -> LDS staging ------------------------------------------------------------
-    const int64_t rstride = (int64_t)a.Hkv * D;
-    const uint16_t* const Kg = a.lv.K + (int64_t)kvh * D;
-    const uint16_t* const Vg = a.lv.V + (int64_t)kvh * D;
-    const int vdp = tid % (D / 2);   // V column pair owned when staging V
-    const int vkg = tid / (D / 2);   // V key group (NK keys each)
+    // ---- HBM -> LDS copies ------------------------------------------------------------------------------
+    // Instruction `i` of wavefront w copies tile rows i*4*RPI + w*RPI + (l / CPR) as one contiguous KiB of
+    // LDS (lane l lands at +16*l); the swizzle is applied on the global side: lane l fetches the chunk
+    // that belongs in its LDS slot.
+    const int64_t rstride = (int64_t)a.Hkv * D;                      // elements between consecutive keys
+    const unsigned rstride_b = (unsigned)rstride * 2u;
+    const int srow = w * RPI + l / CPR;                              // row inside a group of 4*RPI rows
+    const int sch = l % CPR;
+    const unsigned voffK = (unsigned)(l / CPR) * rstride_b + (unsigned)((sch ^ (srow % CPR)) * 16);
+    const unsigned voffV = (unsigned)(l / CPR) * rstride_b + (unsigned)((sch ^ (2 * (srow % VM))) * 16);
+    const unsigned char* const Kg = reinterpret_cast<const unsigned char*>(a.lv.K + (int64_t)kvh * D);
+    const unsigned char* const Vg = reinterpret_cast<const unsigned char*>(a.lv.V + (int64_t)kvh * D);
 
-    uint4 kreg[KCH];
-    uint32_t vreg[NK];
-
-    auto load_tile = [&](int key0) {
-        if (key0 + KT <= ke) {  // whole tile in range (workgroup-uniform): unguarded loads
+    auto copy_tile = [&](int key0, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        unsigned char* kdst = (buf ? sK1 : sK0) + w * (RPI * ROWB);
+        unsigned char* vdst = (buf ? sV1 : sV0) + w * (RPI * ROWB);
+        if (key0 + KT <= ke) {  // whole tile in range (workgroup-uniform)
 #pragma unroll
-            for (int i = 0; i < KCH; ++i) {
-                const int id = tid + 256 * i;
-                kreg[i] = *reinterpret_cast<const uint4*>(Kg + (key0 + id / CPR) * rstride + 8 * (id % CPR));
+            for (int i = 0; i < ROUNDS; ++i) {
+                const int64_t rb = (int64_t)(key0 + i * 4 * RPI + w * RPI) * rstride_b;   // uniform
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Kg + rb + voffK), HG_LDS(kdst + i * (4 * RPI * ROWB)), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Vg + rb + voffV), HG_LDS(vdst + i * (4 * RPI * ROWB)), 16, 0, 0);
             }
+        } else {                // ragged tail: rows past the range re-read row ke-1 (their scores are masked)
 #pragma unroll
-            for (int i = 0; i < NK; ++i)
-                vreg[i] = *reinterpret_cast<const uint32_t*>(Vg + (key0 + vkg * NK + i) * rstride + 2 * vdp);
-        } else {                // ragged tail: rows past the range read row ke-1 and are zeroed
-#pragma unroll
-            for (int i = 0; i < KCH; ++i) {
-                const int id = tid + 256 * i;
-                const int key = key0 + id / CPR;
-                const uint4 v = *reinterpret_cast<const uint4*>(Kg + min(key, ke - 1) * rstride + 8 * (id % CPR));
-                kreg[i] = key < ke ? v : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < NK; ++i) {
-                const int key = key0 + vkg * NK + i;
-                const uint32_t v = *reinterpret_cast<const uint32_t*>(Vg + min(key, ke - 1) * rstride + 2 * vdp);
-                vreg[i] = key < ke ? v : 0u;
+            for (int i = 0; i < ROUNDS; ++i) {
+                const int key = min(key0 + i * 4 * RPI + srow, ke - 1);
+                const int64_t ro = (int64_t)key * rstride_b;
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Kg + ro + (sch ^ (srow % CPR)) * 16), HG_LDS(kdst + i * (4 * RPI * ROWB)), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Vg + ro + (sch ^ (2 * (srow % VM))) * 16), HG_LDS(vdst + i * (4 * RPI * ROWB)), 16, 0, 0);
             }
         }
     };
-    auto store_tile = [&](int buf) {
-        unsigned char* kb = smem + buf * KBYTES;
-        unsigned char* vb = smem + 2 * KBYTES + buf * VBYTES;
+
+    // ---- per-lane LDS read addresses (buffer and sub-block offsets are immediates) -----------------------------
+    // K operand for k-step s: row = 32*sb + lq, chunk 2s+hl
+    unsigned kaddr[KS];
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int id = tid + 256 * i;
-            const int row = id / CPR, c = id % CPR;
-            *reinterpret_cast<uint4*>(kb + row * (D * 2) + ((c ^ (row & (CPR - 1))) * 16)) = kreg[i];
-        }
-        // V^T: row d holds the tile's 64 keys; inside each group of 16 keys, key 8a+4h+b sits at slot 8h+4a+b
+    for (int s = 0; s < KS; ++s) kaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    // V^T operand for d-block db: within each 16-lane group, lane i addresses key (i/4) of the 4 keys being
+    // transposed and columns dbase + 4*(i%4) .. +3; after the transposing read lane i holds column dbase + i
+    // of those 4 keys.  Group (l/16)&1 selects the lower/upper 16 columns, hl the key quad.
+    unsigned vaddr[DB];
+    {
+        const int i16 = l & 15, g1 = (l >> 4) & 1;
+        const int keyq = 4 * hl + (i16 >> 2);                 // key inside an 8-key half step
+        const int fv = 2 * (keyq % VM);
 #pragma unroll
-        for (int qd = 0; qd < NK / 4; ++qd) {
-            const int kq = vkg * NK + 4 * qd;           // first of 4 consecutive keys (tile relative)
-            const int t16 = kq >> 4, aa = (kq >> 3) & 1, hh = (kq >> 2) & 1;
-            const int cv = 2 * t16 + hh;                // 16-byte chunk inside the 128-byte row
-            const uint32_t w0 = vreg[4 * qd], w1 = vreg[4 * qd + 1], w2 = vreg[4 * qd + 2], w3 = vreg[4 * qd + 3];
-            uint2 lo, hi;
-            lo.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
-            lo.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
-            hi.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
-            hi.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-            const int d0 = 2 * vdp, d1 = d0 + 1;
-            *reinterpret_cast<uint2*>(vb + d0 * 128 + ((cv ^ ((d0 >> 1) & 7)) * 16) + 8 * aa) = lo;
-            *reinterpret_cast<uint2*>(vb + d1 * 128 + ((cv ^ ((d1 >> 1) & 7)) * 16) + 8 * aa) = hi;
+        for (int db = 0; db < DB; ++db) {
+            const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);
+            vaddr[db] = (unsigned)(keyq * ROWB + ((chunk ^ fv) * 16) + (i16 & 1) * 8);
         }
-    };
+    }
 
     // ---- online softmax state ----------------------------------------------------------------------------
     floatx16 Oacc[DB];
@@ -177,20 +189,14 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     float lsum = 0.f;           // this lane's share of the row sum
     const float c2 = a.scale * kLog2e;
     const float tau_raw = TAU / c2;
-    float mc = 0.f;             // m_used * c2 (finite stand-in while m_used = -inf is irrelevant: first tile always rescales)
+    float mc = 0.f;             // m_used * c2
 
     const int ntiles = (ke - ks + KT - 1) / KT;
-    load_tile(ks);
-    store_tile(0);
-    __syncthreads();
 
-    for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
-        const bool more = j + 1 < ntiles;
-        if (more) load_tile(ks + (j + 1) * KT);
-
-        const unsigned char* kb = smem + buf * KBYTES;
-        const unsigned char* vb = smem + 2 * KBYTES + buf * VBYTES;
+    auto compute_tile = [&](int j, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        const unsigned char* kb = buf ? sK1 : sK0;
+        const unsigned char* vb = buf ? sV1 : sV0;
 
         // S^T = K Q^T for the two 32-key halves of the tile
         floatx16 S[2];
@@ -198,15 +204,13 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) S[sb][i] = 0.f;
-            const int key = 32 * sb + lq;
-            const unsigned char* krow = kb + key * (D * 2);
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const uint4 kv = *reinterpret_cast<const uint4*>(krow + (((2 * s + hl) ^ (key & (CPR - 1))) * 16));
+                const uint4 kv = *reinterpret_cast<const uint4*>(kb + kaddr[s] + sb * 32 * ROWB);
                 S[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S[sb], 0, 0, 0);
             }
         }
-        if (!more) {  // mask keys beyond the range in the last tile
+        if (j + 1 >= ntiles) {  // mask keys beyond the range in the last tile
             const int base = ks + j * KT + 4 * hl;
 #pragma unroll
             for (int sb = 0; sb < 2; ++sb)
@@ -219,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, S[0][i]);
 #pragma unroll
         for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, S[1][i]);
-        tmax = fmaxf(tmax, other_half(tmax));
+        tmax = half_max(tmax);
 
         if (__any(tmax > m_used + tau_raw)) {
             const float m_new = fmaxf(m_used, tmax);
@@ -251,18 +255,36 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         for (int tt = 0; tt < 4; ++tt) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const int d = 32 * db + lq;
-                const uint4 vv = *reinterpret_cast<const uint4*>(vb + d * 128 + (((2 * tt + hl) ^ ((d >> 1) & 7)) * 16));
+                const unsigned char* vp = vb + vaddr[db] + tt * 16 * ROWB;
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
+                const shortx8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pb[tt], Oacc[db], 0, 0, 0);
             }
         }
+    };
 
-        if (more) store_tile(buf ^ 1);
+    const std::integral_constant<int, 0> B0{};
+    const std::integral_constant<int, 1> B1{};
+    copy_tile(ks, B0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS copies have landed
+    __syncthreads();
+
+    for (int j = 0; j < ntiles; j += 2) {
+        if (j + 1 < ntiles) copy_tile(ks + (j + 1) * KT, B1);
+        compute_tile(j, B0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
+        if (j + 1 < ntiles) {
+            if (j + 2 < ntiles) copy_tile(ks + (j + 2) * KT, B0);
+            compute_tile(j + 1, B1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue ----------------------------------------------------------------------------------------
-    const float ltot = lsum + other_half(lsum);
+    const float ltot = half_sum(lsum);
     if (rv) {
         const float inv = 1.0f / ltot;
 #pragma unroll
@@ -283,19 +305,8 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
 hipError_t launch_prefix(const PrefixArgs& a, int D, hipStream_t s) {
     if (a.total_tiles == 0) return hipSuccess;
     const unsigned grid = (unsigned)a.per_xcd * 8u;
-    const size_t shmem = (size_t)2 * (kPrefixKeys * D * 2) * 2;
-    hipError_t e;
-    if (D == 128) {
-        static bool attr128 = false;
-        if (!attr128) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefix_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-            if (e != hipSuccess) return e;
-            attr128 = true;
-        }
-        prefix_kernel<128><<<grid, 256, shmem, s>>>(a);
-    } else {
-        prefix_kernel<64><<<grid, 256, shmem, s>>>(a);
-    }
+    if (D == 128) prefix_kernel<128><<<grid, 256, 0, s>>>(a);
+    else prefix_kernel<64><<<grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
