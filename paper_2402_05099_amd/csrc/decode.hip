@@ -133,7 +133,9 @@ __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& 
     }
 }
 
-template <int D, int GT>
+// SHARED = false: suffix rows only (the Hydragen suffix part).  SHARED = true: the shared blocks of every level
+// are walked too (the non-decomposed comparison); a separate instantiation so that profiles tell them apart.
+template <int D, int GT, bool SHARED>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     constexpr int LPR = D / 8;
     const int lane = threadIdx.x & 63;
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     // walk the concatenated key list (shared blocks root first, then the suffix), clipped to this chunk
     const int64_t lo = (int64_t)c * a.chunk, hi = lo + a.chunk;
     int64_t pos = 0;
-    for (int li = 0; li < a.n_levels; ++li) {
+    for (int li = 0; SHARED && li < a.n_levels; ++li) {
         int begin, count;
         block_of(a.lv[li], b, a.B, begin, count);
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
@@ -225,7 +227,8 @@ static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     if (a.units == 0) return hipSuccess;
     const int64_t grid = (a.units + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    decode_kernel<D, GT><<<(unsigned)grid, 256, 0, s>>>(a);
+    if (a.n_levels > 0) decode_kernel<D, GT, true><<<(unsigned)grid, 256, 0, s>>>(a);
+    else decode_kernel<D, GT, false><<<(unsigned)grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
