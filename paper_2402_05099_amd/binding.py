@@ -19,7 +19,8 @@ HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING = 1, 2, 3, 4, 5
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhydragen.so")
+# HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)
+LIB_PATH = os.environ.get("HYDRAGEN_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhydragen.so")
 
 # every symbol include/hydragen.h declares
 EXPORTS = (

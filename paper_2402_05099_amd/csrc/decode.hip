@@ -23,6 +23,13 @@ __device__ __forceinline__ float row_allreduce_sum(float x) {
     return x;
 }
 
+// tells the compiler that a pointer is the same in every lane of the wavefront (it then lives in scalar registers)
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
+}
+
 template <int D, int GT>
 struct DecodeState {
     float q[GT][8];    // query elements of this lane's 8-wide column slice, pre-multiplied by scale*log2(e)
@@ -31,83 +38,129 @@ struct DecodeState {
     float acc[GT][8];  // running sum of 2^(s-m) * v
 };
 
-// Online-softmax pass over `n` consecutive KV rows starting at row0, KV head kvh.
+// One batch of U wave-wide loads: KPW keys each, K and V rows of this lane's 8-column slice.
+template <int D, int U>
+struct KVBatch {
+    uint4 k[U], v[U];
+};
+
+// 16-byte load from global memory at uniform base + 32-bit lane offset (scalar base register + vector offset form)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldg128(const unsigned char* base, unsigned off) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(
+        (const __attribute__((address_space(1))) unsigned char*)base + off));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// kb/vb: wavefront-uniform byte pointers to the span's first row of this KV head; rowoff: this lane's byte offset
+// of its key in load 0 of the batch (sub-row, column slice and batch start); colb: the column part alone.  Lanes
+// whose key lies past the span read the span's first row instead (always valid; their score is masked), so no
+// load is predicated and a batch may be requested past the end of the span.
+template <int D, int U>
+__device__ __forceinline__ void load_batch(KVBatch<D, U>& bt, const unsigned char* __restrict__ kb,
+                                           const unsigned char* __restrict__ vb, unsigned rstride_b, unsigned rowoff,
+                                           unsigned colb, int first, int n) {
+    constexpr int KPW = 64 / (D / 8);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = first + u * KPW;   // `first` already includes this lane's sub-row
+        const unsigned off = i < n ? (unsigned)(u * KPW) * rstride_b + rowoff : colb;
+        bt.k[u] = ldg128(kb, off);
+        bt.v[u] = ldg128(vb, off);
+    }
+}
+
+// online-softmax update of the state with one batch (keys first + u*KPW, masked beyond n)
+template <int D, int GT, int U>
+__device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBatch<D, U>& bt, int first, int n) {
+    constexpr int LPR = D / 8;
+    constexpr int KPW = 64 / LPR;
+    float s[U][GT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const bool ok = first + u * KPW < n;
+        const uint4 kr = bt.k[u];
+        const float k0 = bf16_lo(kr.x), k1 = bf16_hi(kr.x), k2 = bf16_lo(kr.y), k3 = bf16_hi(kr.y);
+        const float k4 = bf16_lo(kr.z), k5 = bf16_hi(kr.z), k6 = bf16_lo(kr.w), k7 = bf16_hi(kr.w);
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            float d = st.q[g][0] * k0;
+            d = fmaf(st.q[g][1], k1, d);
+            d = fmaf(st.q[g][2], k2, d);
+            d = fmaf(st.q[g][3], k3, d);
+            d = fmaf(st.q[g][4], k4, d);
+            d = fmaf(st.q[g][5], k5, d);
+            d = fmaf(st.q[g][6], k6, d);
+            d = fmaf(st.q[g][7], k7, d);
+            d = row_allreduce_sum<LPR>(d);
+            s[u][g] = ok ? d : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        float mx = st.m[g];
+#pragma unroll
+        for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[u][g]);
+        const float ms = (mx == -INFINITY) ? 0.f : mx;
+        const float alpha = __builtin_amdgcn_exp2f(st.m[g] - ms);
+        st.m[g] = mx;
+        float p[U];
+        float ps = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            p[u] = __builtin_amdgcn_exp2f(s[u][g] - ms);
+            ps += p[u];
+        }
+        st.l[g] = fmaf(st.l[g], alpha, ps);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[g][j] *= alpha;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint4 vr = bt.v[u];
+            st.acc[g][0] = fmaf(p[u], bf16_lo(vr.x), st.acc[g][0]);
+            st.acc[g][1] = fmaf(p[u], bf16_hi(vr.x), st.acc[g][1]);
+            st.acc[g][2] = fmaf(p[u], bf16_lo(vr.y), st.acc[g][2]);
+            st.acc[g][3] = fmaf(p[u], bf16_hi(vr.y), st.acc[g][3]);
+            st.acc[g][4] = fmaf(p[u], bf16_lo(vr.z), st.acc[g][4]);
+            st.acc[g][5] = fmaf(p[u], bf16_hi(vr.z), st.acc[g][5]);
+            st.acc[g][6] = fmaf(p[u], bf16_lo(vr.w), st.acc[g][6]);
+            st.acc[g][7] = fmaf(p[u], bf16_hi(vr.w), st.acc[g][7]);
+        }
+    }
+}
+
+// Online-softmax pass over `n` consecutive KV rows starting at row0, KV head kvh.  Software pipelined: the
+// loads of the next batch are issued before the current batch is consumed, so a wavefront always has a
+// batch in flight while it computes.
 template <int D, int GT>
 __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
                                             const uint16_t* __restrict__ V, int64_t row0, int n, int Hkv, int kvh,
                                             int lane) {
     constexpr int LPR = D / 8;
     constexpr int KPW = 64 / LPR;
-    constexpr int U = 4;
+    constexpr int U = GT >= 8 ? 2 : 4;
+    constexpr int STEP = KPW * U;
     const int sub = lane / LPR;
-    const int col = (lane % LPR) * 8;
-    const int64_t rstride = (int64_t)Hkv * D;
-    const uint16_t* kbase = K + (row0 * Hkv + kvh) * (int64_t)D + col;
-    const uint16_t* vbase = V + (row0 * Hkv + kvh) * (int64_t)D + col;
+    const unsigned rstride_b = (unsigned)Hkv * D * 2u;
+    const unsigned colb = (unsigned)(lane % LPR) * 16u;
+    unsigned rowoff = (unsigned)sub * rstride_b + colb;
+    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K + (row0 * Hkv + kvh) * (int64_t)D));
+    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V + (row0 * Hkv + kvh) * (int64_t)D));
+    const unsigned step_b = (unsigned)STEP * rstride_b;
 
-    for (int it = 0; it < n; it += KPW * U) {
-        uint4 kr[U], vr[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = it + u * KPW + sub;
-            ok[u] = i < n;
-            kr[u] = make_uint4(0, 0, 0, 0);
-            vr[u] = make_uint4(0, 0, 0, 0);
-            if (ok[u]) {
-                kr[u] = *reinterpret_cast<const uint4*>(kbase + i * rstride);
-                vr[u] = *reinterpret_cast<const uint4*>(vbase + i * rstride);
-            }
-        }
-        float s[U][GT];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float k0 = bf16_lo(kr[u].x), k1 = bf16_hi(kr[u].x), k2 = bf16_lo(kr[u].y), k3 = bf16_hi(kr[u].y);
-            const float k4 = bf16_lo(kr[u].z), k5 = bf16_hi(kr[u].z), k6 = bf16_lo(kr[u].w), k7 = bf16_hi(kr[u].w);
-#pragma unroll
-            for (int g = 0; g < GT; ++g) {
-                float d = st.q[g][0] * k0;
-                d = fmaf(st.q[g][1], k1, d);
-                d = fmaf(st.q[g][2], k2, d);
-                d = fmaf(st.q[g][3], k3, d);
-                d = fmaf(st.q[g][4], k4, d);
-                d = fmaf(st.q[g][5], k5, d);
-                d = fmaf(st.q[g][6], k6, d);
-                d = fmaf(st.q[g][7], k7, d);
-                d = row_allreduce_sum<LPR>(d);
-                s[u][g] = ok[u] ? d : -INFINITY;
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float mx = st.m[g];
-#pragma unroll
-            for (int u = 0; u < U; ++u) mx = fmaxf(mx, s[u][g]);
-            const float ms = (mx == -INFINITY) ? 0.f : mx;
-            const float alpha = __builtin_amdgcn_exp2f(st.m[g] - ms);
-            st.m[g] = mx;
-            float p[U];
-            float ps = 0.f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                p[u] = __builtin_amdgcn_exp2f(s[u][g] - ms);
-                ps += p[u];
-            }
-            st.l[g] = fmaf(st.l[g], alpha, ps);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) st.acc[g][j] *= alpha;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                st.acc[g][0] = fmaf(p[u], bf16_lo(vr[u].x), st.acc[g][0]);
-                st.acc[g][1] = fmaf(p[u], bf16_hi(vr[u].x), st.acc[g][1]);
-                st.acc[g][2] = fmaf(p[u], bf16_lo(vr[u].y), st.acc[g][2]);
-                st.acc[g][3] = fmaf(p[u], bf16_hi(vr[u].y), st.acc[g][3]);
-                st.acc[g][4] = fmaf(p[u], bf16_lo(vr[u].z), st.acc[g][4]);
-                st.acc[g][5] = fmaf(p[u], bf16_hi(vr[u].z), st.acc[g][5]);
-                st.acc[g][6] = fmaf(p[u], bf16_lo(vr[u].w), st.acc[g][6]);
-                st.acc[g][7] = fmaf(p[u], bf16_hi(vr[u].w), st.acc[g][7]);
-            }
-        }
+    // every load is issued unconditionally (see load_batch), so the wait counts the compiler derives are exact
+    KVBatch<D, U> ba, bb;
+    load_batch<D, U>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
+    for (int it = 0; it < n; it += 2 * STEP) {
+        rowoff += step_b;
+        load_batch<D, U>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
+        __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic that hides their latency
+        consume_batch<D, GT, U>(st, ba, it + sub, n);
+        rowoff += step_b;
+        __builtin_amdgcn_sched_barrier(0);
+        load_batch<D, U>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + STEP < n) consume_batch<D, GT, U>(st, bb, it + STEP + sub, n);
     }
 }
 
