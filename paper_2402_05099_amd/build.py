@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhydragen.so")
-SOURCES = ["api.hip", "prefix.hip", "decode.hip", "merge.hip"]
+SOURCES = ["api.hip", "prefix.hip", "prefix_wide.hip", "decode.hip", "merge.hip"]
 
 # packed fp32 VALU forms are switched off for every device compile of this library
 HIPCC_FLAGS = [
@@ -26,13 +26,35 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# per-source extra flags: the wide shared-block kernel keeps its score MFMAs in architectural VGPRs (its value
+# accumulators sit in fixed AGPRs managed by hand), which needs the VGPR form of MFMA selection
+PER_SOURCE_FLAGS = {"prefix_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def build(verbose: bool = True, extra_flags=()) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    """Compile every source to an object (sources may carry their own flags), then link the shared library."""
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    cc = hipcc()
+    common = [f for f in HIPCC_FLAGS if f != "-shared"]
+    objs = []
+    procs = []
+    for src in SOURCES:
+        obj = os.path.join(objdir, src + ".o")
+        cmd = [cc, *common, *PER_SOURCE_FLAGS.get(src, []), *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+               "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((cmd, subprocess.Popen(cmd)))
+        objs.append(obj)
+    for cmd, pr in procs:
+        if pr.wait() != 0:
+            raise subprocess.CalledProcessError(pr.returncode, cmd)
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp, *srcs]
+    link = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+        print(" ".join(link), flush=True)
+    subprocess.check_call(link)
     os.replace(tmp, LIB)
     return LIB
 

@@ -14,6 +14,7 @@ struct hg_ctx {
     int opt_suffix_chunk;
     int opt_overlap;
     int opt_naive_chunk;
+    int opt_prefix_kernel;
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -90,43 +91,60 @@ int pick_gt(int G) {
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
 
-// default number of key-range splits for one level
-int default_splits(const hg_ctx* c, const LevelDev& lv, int Hkv, int G) {
-    if (lv.max_rows <= 0) return 1;
+// which shared-block kernel runs a level, and over how many key-range splits
+struct LevelPlan { bool wide; int ns; };
+
+// The wide kernel (256 rows per workgroup, one workgroup per CU) needs D = 128 and pays off once a block has
+// at least one full tile of query rows; otherwise the 128-row kernel (two workgroups per CU) runs.
+LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D) {
+    LevelPlan p;
+    const int rows = lv.max_seqs * G;
+    p.wide = D == 128 && (c->opt_prefix_kernel == 2 || (c->opt_prefix_kernel == 0 && rows >= kPrefixRowsWide));
+    p.ns = 1;
+    if (lv.max_rows <= 0) return p;
+    const int tile_rows = p.wide ? kPrefixRowsWide : kPrefixRowsNarrow;
+    const int slots = p.wide ? 256 : 512;   // workgroups resident on the 256 CUs
+    const int64_t base = (int64_t)lv.n_blocks * ceil_div(rows, tile_rows) * Hkv;
+    const int max_ns = ceil_div(lv.max_rows, kPrefixKeys);
     int ns;
     if (c->opt_prefix_splits > 0) {
         ns = c->opt_prefix_splits;
     } else {
-        const int64_t base = (int64_t)lv.n_blocks * ceil_div(lv.max_seqs * G, kPrefixRows) * Hkv;
-        ns = (int)((1536 + base - 1) / (base > 0 ? base : 1));
-        const int by_len = lv.max_rows / 256;
-        if (ns > by_len) ns = by_len;
-        if (ns > 16) ns = 16;
+        // fill whole rounds of resident workgroups: pick the split count (chunks of >= 512 keys, <= 16 splits)
+        // with the best occupancy of the last round, preferring fewer splits (each adds merge traffic)
+        ns = 1;
+        double best = -1.0;
+        const int lim = lv.max_rows / 512 < 16 ? lv.max_rows / 512 : 16;
+        for (int n = 1; n <= (lim > 1 ? lim : 1); ++n) {
+            const int64_t wgs = base * n;
+            const int64_t rounds = (wgs + slots - 1) / slots;
+            const double eff = (double)wgs / (double)(rounds * slots) - 0.01 * n + (rounds >= 3 ? 0.05 : 0.0);
+            if (eff > best) { best = eff; ns = n; }
+        }
     }
-    const int max_ns = ceil_div(lv.max_rows, kPrefixKeys);
     if (ns > max_ns) ns = max_ns;
     if (ns < 1) ns = 1;
-    return ns;
+    p.ns = ns;
+    return p;
 }
 
 // enqueue the shared-block kernel for one level with `ns` splits writing to `out` (part = split)
-int run_level(const hg_ctx* c, const void* Q, const LevelDev& lv, int ns, int B, int Hq, int Hkv, int D, float scale,
+int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int Hq, int Hkv, int D, float scale,
               const OutDev& out, hipStream_t s) {
     PrefixArgs a{};
     a.Q = static_cast<const uint16_t*>(Q);
     a.lv = lv;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
-    a.mtiles = ceil_div(lv.max_seqs * a.G, kPrefixRows);
-    a.nsplit = ns;
-    a.chunk = round_up(ceil_div(lv.max_rows > 0 ? lv.max_rows : 1, ns), kPrefixKeys);
-    const int64_t total = (int64_t)lv.n_blocks * ns * Hkv * a.mtiles;
+    a.mtiles = ceil_div(lv.max_seqs * a.G, plan.wide ? kPrefixRowsWide : kPrefixRowsNarrow);
+    a.nsplit = plan.ns;
+    a.chunk = round_up(ceil_div(lv.max_rows > 0 ? lv.max_rows : 1, plan.ns), kPrefixKeys);
+    const int64_t total = (int64_t)lv.n_blocks * plan.ns * Hkv * a.mtiles;
     if (total >= (1LL << 28)) return HG_ERR_UNSUPPORTED;
     a.total_tiles = (int)total;
     a.per_xcd = ceil_div(a.total_tiles, 8);
     a.scale = scale;
     a.out = out;
-    (void)c;
-    return hip_rc(launch_prefix(a, D, s));
+    return hip_rc(plan.wide ? launch_prefix_wide(a, s) : launch_prefix_narrow(a, D, s));
 }
 
 struct SuffixPlan { int chunk, nchunks, gt; };
@@ -212,7 +230,7 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->ws = static_cast<unsigned char*>(workspace);
     c->ws_bytes = workspace_bytes;
-    c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = 0;
+    c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = c->opt_prefix_kernel = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -256,6 +274,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_SUFFIX_CHUNK: c->opt_suffix_chunk = value; return HG_OK;
         case HG_OPT_OVERLAP: c->opt_overlap = value; return HG_OK;
         case HG_OPT_NAIVE_CHUNK: c->opt_naive_chunk = value; return HG_OK;
+        case HG_OPT_PREFIX_KERNEL:
+            if (value > 2) return HG_ERR_INVALID_ARG;
+            c->opt_prefix_kernel = value;
+            return HG_OK;
         case HG_OPT_STAGE_TIMING:
             if (value && !c->tev) {
                 if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
@@ -293,8 +315,9 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     const int64_t rows = (int64_t)B * Hq;
     const LevelDev lv = to_dev(*level, B);
     const Parts parts = carve(c, rows, D);
-    int ns = default_splits(c, lv, Hkv, Hq / Hkv);
-    if (ns > parts.cap) ns = parts.cap > 1 ? parts.cap : 1;
+    LevelPlan plan = plan_level(c, lv, Hkv, Hq / Hkv, D);
+    if (plan.ns > parts.cap) plan.ns = parts.cap > 1 ? parts.cap : 1;
+    const int ns = plan.ns;
     hipStream_t s = c->stream;
     if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     if (ns == 1) {
@@ -302,13 +325,13 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
             rc = fill_empty(O, o_dtype, LSE, rows, D, s);
             if (rc) return rc;
         }
-        return run_level(c, Q, lv, 1, B, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
+        return run_level(Q, lv, plan, B, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
     }
     if (lv.seq_off) {
         rc = fill_empty(nullptr, HG_F32, parts.l(0), rows * ns, D, s);
         if (rc) return rc;
     }
-    rc = run_level(c, Q, lv, ns, B, Hq, Hkv, D, scale, parts_out(parts, 0), s);
+    rc = run_level(Q, lv, plan, B, Hq, Hkv, D, scale, parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(ns, parts, 0, D, O, o_dtype, LSE, s);
 }
@@ -404,13 +427,15 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
 
     // plan: parts per level and for the suffix, shrunk to fit the workspace
     LevelDev lv[HG_MAX_LEVELS];
+    LevelPlan plan[HG_MAX_LEVELS];
     int ns[HG_MAX_LEVELS];
     int nlev = 0;
     for (int i = 0; i < n_levels; ++i) {
         LevelDev d = to_dev(levels[i], B);
         if (d.max_rows == 0 || d.max_seqs == 0) continue;  // empty level contributes nothing
         lv[nlev] = d;
-        ns[nlev] = default_splits(c, d, Hkv, G);
+        plan[nlev] = plan_level(c, d, Hkv, G, D);
+        ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
     SuffixPlan sp = plan_suffix(c, max_len, G);
@@ -473,7 +498,8 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
     first = 0;
     for (int i = 0; i < nlev; ++i) {
         if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
-        rc = run_level(c, Q, lv[i], ns[i], B, Hq, Hkv, D, scale, parts_out(parts, first), s);
+        plan[i].ns = ns[i];
+        rc = run_level(Q, lv[i], plan[i], B, Hq, Hkv, D, scale, parts_out(parts, first), s);
         if (rc) return rc;
         if (!mark(1 + i, 1, s)) return HG_ERR_HIP;
         first += ns[i];

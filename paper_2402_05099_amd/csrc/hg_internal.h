@@ -75,13 +75,15 @@ struct FillArgs {
 };
 
 // ---- launchers (defined next to their kernels) ------------------------------------------------------
-hipError_t launch_prefix(const PrefixArgs& a, int D, hipStream_t s);
+hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s);
+hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 
-constexpr int kPrefixRows = 128;  // query rows per prefix workgroup
-constexpr int kPrefixKeys = 64;   // keys per prefix LDS tile
+constexpr int kPrefixRowsNarrow = 128;  // query rows per workgroup, 32-rows-per-wavefront kernel
+constexpr int kPrefixRowsWide = 256;    // query rows per workgroup, 64-rows-per-wavefront kernel
+constexpr int kPrefixKeys = 64;         // keys per prefix LDS tile
 
 // ---- small device helpers -------------------------------------------------------------------------
 #ifdef __HIPCC__

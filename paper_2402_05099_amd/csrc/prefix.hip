@@ -19,28 +19,9 @@
 #include <type_traits>
 
 #include "hg_internal.h"
+#include "prefix_common.h"
 
 namespace hg {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx8 __attribute__((ext_vector_type(8)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-typedef short shortx8 __attribute__((ext_vector_type(8)));
-
-#define HG_LDS(p) ((__attribute__((address_space(3))) unsigned char*)(p))
-#define HG_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
-
-// Value held by the lane 32 positions away.  v_permlane32_swap exchanges the upper 32 lanes of its first
-// operand with the lower 32 lanes of its second, so the partner's value arrives in the first result for
-// the upper half of the wavefront and in the second result for the lower half.
-__device__ __forceinline__ float other_half(float x) {
-    const unsigned u = __builtin_bit_cast(unsigned, x);
-    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
-}
-__device__ __forceinline__ float half_max(float x) { return fmaxf(x, other_half(x)); }
-__device__ __forceinline__ float half_sum(float x) { return x + other_half(x); }
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
@@ -82,7 +63,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         kv1 = min(a.lv.kv_off[g + 1], kv0 + a.lv.max_rows);
     }
     const int nrows = (seq1 - seq0) * a.G;
-    const int row0 = mt * kPrefixRows;
+    const int row0 = mt * kPrefixRowsNarrow;
     if (row0 >= nrows) return;
     const int ks = kv0 + sp * a.chunk;
     const int ke = min(ks + a.chunk, kv1);
@@ -302,7 +283,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     }
 }
 
-hipError_t launch_prefix(const PrefixArgs& a, int D, hipStream_t s) {
+hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s) {
     if (a.total_tiles == 0) return hipSuccess;
     const unsigned grid = (unsigned)a.per_xcd * 8u;
     if (D == 128) prefix_kernel<128><<<grid, 256, 0, s>>>(a);

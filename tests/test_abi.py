@@ -45,7 +45,7 @@ def test_constants_match_header():
     text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
     for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_F32", "HG_BF16",
                  "HG_MAX_LEVELS", "HG_MAX_PARTS", "HG_OPT_PREFIX_SPLITS", "HG_OPT_SUFFIX_CHUNK", "HG_OPT_OVERLAP",
-                 "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_TIMING_RING"):
+                 "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_OPT_PREFIX_KERNEL", "HG_TIMING_RING"):
         m = re.search(rf"\b{name}\s*=\s*(\d+)", text)
         assert m, name
         assert int(m.group(1)) == getattr(hb, name), name

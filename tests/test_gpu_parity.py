@@ -93,10 +93,12 @@ def test_suffix_attn(idx, chunk):
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
 @pytest.mark.parametrize("splits", [0, 1, 3])
-def test_prefix_attn(idx, splits):
-    say(f"prefix idx={idx} splits={splits}")
+@pytest.mark.parametrize("kernel", [1, 2], ids=["rows128", "rows256"])
+def test_prefix_attn(idx, splits, kernel):
+    say(f"prefix idx={idx} splits={splits} kernel={kernel}")
     w, dw = workload(idx)
     ctx = dev.make_context(dw, parts=8)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)   # 2 is honoured for D = 128 only
     if splits:
         ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
     Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
@@ -110,10 +112,12 @@ def test_prefix_attn(idx, splits):
 
 
 @pytest.mark.parametrize("splits", [0, 2])
-def test_prefix_attn_grouped_tree_levels(splits):
-    say(f"grouped splits={splits}")
+@pytest.mark.parametrize("kernel", [1, 2], ids=["rows128", "rows256"])
+def test_prefix_attn_grouped_tree_levels(splits, kernel):
+    say(f"grouped splits={splits} kernel={kernel}")
     w, dw = workload(5)
     ctx = dev.make_context(dw, parts=8)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
     if splits:
         ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
     for li in (0, 1):
@@ -156,10 +160,12 @@ VARIANTS = [dict(), dict(q_gain=4.0), dict(plant="suffix"), dict(plant="prefix")
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("variant", VARIANTS, ids=["normal", "peaked", "plant_suffix", "plant_prefix"])
-def test_fused_hydragen_and_naive(idx, variant):
-    say(f"fused idx={idx} {variant}")
+@pytest.mark.parametrize("kernel", [0, 2], ids=["auto", "rows256"])
+def test_fused_hydragen_and_naive(idx, variant, kernel):
+    say(f"fused idx={idx} {variant} kernel={kernel}")
     w, dw = workload(idx, **variant)
     ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
     Oref, Lref = oracle.attention(w)
     for dtype in (torch.bfloat16, torch.float32):
         O, L, intact = outputs(dw, dtype)
