@@ -59,10 +59,10 @@ enum { HG_MAX_LEVELS = 4, HG_MAX_PARTS = 64 };
 enum {
     HG_OPT_PREFIX_SPLITS = 1, /* number of key-range splits of each shared block (>=1) */
     HG_OPT_SUFFIX_CHUNK = 2,  /* keys per work item of the suffix kernel (multiple of 32) */
-    HG_OPT_OVERLAP = 3,       /* 1: run shared-block and suffix kernels on two streams inside the fused call */
+    HG_OPT_OVERLAP = 3,       /* fused call: 0 shared-block and suffix kernels overlap on two streams, 1 one stream, 2 two streams with the shared-block kernels enqueued first */
     HG_OPT_NAIVE_CHUNK = 4,   /* keys per work item of the non-decomposed comparison kernel */
     HG_OPT_STAGE_TIMING = 5,  /* 1: hg_hydragen_attn brackets each of its kernels with timing events */
-    HG_OPT_PREFIX_KERNEL = 6  /* shared-block kernel: 0 automatic, 1 128-row workgroups, 2 256-row workgroups (D = 128) */
+    HG_OPT_PREFIX_KERNEL = 6  /* shared-block kernel: 0 or 1 128-row workgroups, 2 256-row workgroups (D = 128 only) */
 };
 enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };
 

@@ -26,9 +26,7 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-# per-source extra flags: the wide shared-block kernel keeps its score MFMAs in architectural VGPRs (its value
-# accumulators sit in fixed AGPRs managed by hand), which needs the VGPR form of MFMA selection
-PER_SOURCE_FLAGS = {"prefix_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+PER_SOURCE_FLAGS = {}   # source file name -> extra hipcc flags
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:

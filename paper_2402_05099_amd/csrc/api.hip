@@ -94,12 +94,12 @@ int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
 // which shared-block kernel runs a level, and over how many key-range splits
 struct LevelPlan { bool wide; int ns; };
 
-// The wide kernel (256 rows per workgroup, one workgroup per CU) needs D = 128 and pays off once a block has
-// at least one full tile of query rows; otherwise the 128-row kernel (two workgroups per CU) runs.
+// The 128-row kernel (two workgroups per CU, ~200 VGPRs) is the default: it leaves register space on every SIMD
+// for suffix wavefronts to run beside it.  The 256-row kernel (D = 128 only) is selected by option.
 LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D) {
     LevelPlan p;
     const int rows = lv.max_seqs * G;
-    p.wide = D == 128 && (c->opt_prefix_kernel == 2 || (c->opt_prefix_kernel == 0 && rows >= kPrefixRowsWide));
+    p.wide = D == 128 && c->opt_prefix_kernel == 2;
     p.ns = 1;
     if (lv.max_rows <= 0) return p;
     const int tile_rows = p.wide ? kPrefixRowsWide : kPrefixRowsNarrow;
@@ -110,17 +110,12 @@ LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D)
     if (c->opt_prefix_splits > 0) {
         ns = c->opt_prefix_splits;
     } else {
-        // fill whole rounds of resident workgroups: pick the split count (chunks of >= 512 keys, <= 16 splits)
-        // with the best occupancy of the last round, preferring fewer splits (each adds merge traffic)
-        ns = 1;
-        double best = -1.0;
-        const int lim = lv.max_rows / 512 < 16 ? lv.max_rows / 512 : 16;
-        for (int n = 1; n <= (lim > 1 ? lim : 1); ++n) {
-            const int64_t wgs = base * n;
-            const int64_t rounds = (wgs + slots - 1) / slots;
-            const double eff = (double)wgs / (double)(rounds * slots) - 0.01 * n + (rounds >= 3 ? 0.05 : 0.0);
-            if (eff > best) { best = eff; ns = n; }
-        }
+        // enough workgroups for about two full rounds of the resident slots, in chunks of at least 512 keys;
+        // every extra split adds a partial result for the merge to read
+        ns = (int)((2 * slots + base - 1) / (base > 0 ? base : 1));
+        const int by_len = lv.max_rows / 512;
+        if (ns > by_len) ns = by_len;
+        if (ns > 16) ns = 16;
     }
     if (ns > max_ns) ns = max_ns;
     if (ns < 1) ns = 1;
@@ -272,7 +267,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
     switch (option) {
         case HG_OPT_PREFIX_SPLITS: c->opt_prefix_splits = value; return HG_OK;
         case HG_OPT_SUFFIX_CHUNK: c->opt_suffix_chunk = value; return HG_OK;
-        case HG_OPT_OVERLAP: c->opt_overlap = value; return HG_OK;
+        case HG_OPT_OVERLAP:
+            if (value > 2) return HG_ERR_INVALID_ARG;
+            c->opt_overlap = value;
+            return HG_OK;
         case HG_OPT_NAIVE_CHUNK: c->opt_naive_chunk = value; return HG_OK;
         case HG_OPT_PREFIX_KERNEL:
             if (value > 2) return HG_ERR_INVALID_ARG;
@@ -469,7 +467,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         first += ns[i];
     }
 
-    const bool overlap = c->opt_overlap && has_suffix && nlev > 0;
+    const bool overlap = c->opt_overlap != 1 && has_suffix && nlev > 0;   // 0 automatic = two streams
     hipStream_t ssfx = s;
     if (overlap) {
         if (hipEventRecord(c->ev_fork, s) != hipSuccess) return HG_ERR_HIP;
@@ -485,24 +483,43 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         c->tused[slot * HG_MAX_STAGES + stage] = 1;
         return hipEventRecord(c->tev[(slot * HG_MAX_STAGES + stage) * 2 + which], st) == hipSuccess;
     };
-    first = 0;
-    for (int i = 0; i < nlev; ++i) first += ns[i];
-    if (has_suffix) {
+    int suffix_first = 0;
+    for (int i = 0; i < nlev; ++i) suffix_first += ns[i];
+    auto enqueue_suffix = [&]() -> int {
+        if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
-        rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, sp.chunk, sp.nchunks,
-                        sp.gt, parts_out(parts, first), ssfx);
-        if (rc) return rc;
+        const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, sp.chunk,
+                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx);
+        if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
-    }
-    first = 0;
-    for (int i = 0; i < nlev; ++i) {
-        if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
-        plan[i].ns = ns[i];
-        rc = run_level(Q, lv[i], plan[i], B, Hq, Hkv, D, scale, parts_out(parts, first), s);
+        return HG_OK;
+    };
+    auto enqueue_levels = [&]() -> int {
+        int part = 0;
+        for (int i = 0; i < nlev; ++i) {
+            if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
+            plan[i].ns = ns[i];
+            const int r = run_level(Q, lv[i], plan[i], B, Hq, Hkv, D, scale, parts_out(parts, part), s);
+            if (r) return r;
+            if (!mark(1 + i, 1, s)) return HG_ERR_HIP;
+            part += ns[i];
+        }
+        return HG_OK;
+    };
+    // HG_OPT_OVERLAP 2 enqueues the shared-block kernels before the suffix kernel; otherwise the suffix kernel goes
+    // first.  Either way the memory-bound suffix wavefronts and the matrix-bound shared-block workgroups share the
+    // CUs (the latter leave register space for the former on every SIMD).
+    if (c->opt_overlap == 2) {
+        rc = enqueue_levels();
         if (rc) return rc;
-        if (!mark(1 + i, 1, s)) return HG_ERR_HIP;
-        first += ns[i];
+        rc = enqueue_suffix();
+        if (rc) return rc;
+    } else {
+        rc = enqueue_suffix();
+        if (rc) return rc;
+        rc = enqueue_levels();
+        if (rc) return rc;
     }
     if (overlap && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HG_ERR_HIP;
     if (!mark(nlev + 1, 0, s)) return HG_ERR_HIP;
