@@ -24,9 +24,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
-# (kernel, workload); None until measured for that pair.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/fused_c3_P16384_hbm_traffic.txt),
+# each counter scaled by its reading for a 1 GiB device copy (FETCH_SIZE reads 0.50003 of the true KiB on this
+# chip, WRITE_SIZE 1.0), keyed by (kernel, workload); None for pairs not measured.
+MEASURED_TRAFFIC = {
+    ("prefix_level0", "c3_long_P16384"): int((184594.3 / 0.50003 + 83430.6) * 1024),
+    ("suffix", "c3_long_P16384"): int((834118.2 / 0.50003 + 20803.0) * 1024),
+}
 
 
 def main() -> int:
@@ -42,6 +46,8 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=0, help="HG_OPT_OVERLAP: 0 library default (two streams), 1 one stream, 2 two streams, shared blocks first")
     ap.add_argument("--suffix-chunk", type=int, default=0)
     ap.add_argument("--parts", type=int, default=24)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--prefix-kernel", type=int, default=0, help="0 auto, 1 128-row workgroups, 2 256-row workgroups")
     args = ap.parse_args()
 
@@ -85,6 +91,13 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy_mib > 0:   # a copy kernel of known size: reads and writes exactly this many bytes
+        src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def timed(n):
         """n fused calls bracketed by synchronisation; returns (ms per step, mean stage ms [suffix, levels.., merge])"""

@@ -46,9 +46,13 @@ struct KVBatch {
 
 // 16-byte load from global memory at uniform base + 32-bit lane offset (scalar base register + vector offset form)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// STREAM: rows read exactly once (suffix KV) bypass the caches' retention; shared rows are loaded normally so that
+// the re-reads of other sequences can hit in L2 / Infinity Cache
+template <bool STREAM>
 __device__ __forceinline__ uint4 ldg128(const unsigned char* base, unsigned off) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(
-        (const __attribute__((address_space(1))) unsigned char*)base + off));
+    const auto* p = reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(
+        (const __attribute__((address_space(1))) unsigned char*)base + off);
+    const u32x4 v = STREAM ? __builtin_nontemporal_load(p) : *p;
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -56,7 +60,7 @@ __device__ __forceinline__ uint4 ldg128(const unsigned char* base, unsigned off)
 // of its key in load 0 of the batch (sub-row, column slice and batch start); colb: the column part alone.  Lanes
 // whose key lies past the span read the span's first row instead (always valid; their score is masked), so no
 // load is predicated and a batch may be requested past the end of the span.
-template <int D, int U>
+template <int D, int U, bool STREAM>
 __device__ __forceinline__ void load_batch(KVBatch<D, U>& bt, const unsigned char* __restrict__ kb,
                                            const unsigned char* __restrict__ vb, unsigned rstride_b, unsigned rowoff,
                                            unsigned colb, int first, int n) {
@@ -65,8 +69,8 @@ __device__ __forceinline__ void load_batch(KVBatch<D, U>& bt, const unsigned cha
     for (int u = 0; u < U; ++u) {
         const int i = first + u * KPW;   // `first` already includes this lane's sub-row
         const unsigned off = i < n ? (unsigned)(u * KPW) * rstride_b + rowoff : colb;
-        bt.k[u] = ldg128(kb, off);
-        bt.v[u] = ldg128(vb, off);
+        bt.k[u] = ldg128<STREAM>(kb, off);
+        bt.v[u] = ldg128<STREAM>(vb, off);
     }
 }
 
@@ -132,7 +136,7 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBa
 // Online-softmax pass over `n` consecutive KV rows starting at row0, KV head kvh.  Software pipelined: the
 // loads of the next batch are issued before the current batch is consumed, so a wavefront always has a
 // batch in flight while it computes.
-template <int D, int GT>
+template <int D, int GT, bool STREAM>
 __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
                                             const uint16_t* __restrict__ V, int64_t row0, int n, int Hkv, int kvh,
                                             int lane) {
@@ -150,15 +154,15 @@ __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16
 
     // every load is issued unconditionally (see load_batch), so the wait counts the compiler derives are exact
     KVBatch<D, U> ba, bb;
-    load_batch<D, U>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
+    load_batch<D, U, STREAM>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
     for (int it = 0; it < n; it += 2 * STEP) {
         rowoff += step_b;
-        load_batch<D, U>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
+        load_batch<D, U, STREAM>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic that hides their latency
         consume_batch<D, GT, U>(st, ba, it + sub, n);
         rowoff += step_b;
         __builtin_amdgcn_sched_barrier(0);
-        load_batch<D, U>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
+        load_batch<D, U, STREAM>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);
         if (it + STEP < n) consume_batch<D, GT, U>(st, bb, it + STEP + sub, n);
     }
@@ -227,14 +231,14 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         int begin, count;
         block_of(a.lv[li], b, a.B, begin, count);
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
-        if (s0 < s1) decode_span<D, GT>(st, a.lv[li].K, a.lv[li].V, begin + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+        if (s0 < s1) decode_span<D, GT, false>(st, a.lv[li].K, a.lv[li].V, begin + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
         pos += count;
     }
     if (a.lengths) {
         int count = min(a.lengths[b], a.max_len);
         if (count < 0) count = 0;
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
-        if (s0 < s1) decode_span<D, GT>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+        if (s0 < s1) decode_span<D, GT, true>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
     }
 
     // combine the 64/LPR key sub-streams of the wavefront and write (O, LSE)
