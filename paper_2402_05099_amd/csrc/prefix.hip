@@ -33,13 +33,16 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     constexpr int ROUNDS = KT / (4 * RPI); // such instructions per wavefront per tile and tensor
     constexpr int ROWB = D * 2;            // bytes per row
     constexpr int TILEB = KT * ROWB;       // bytes per K (or V) tile
-    constexpr int VM = CPR / 2;            // 32-byte chunk pairs per row (V swizzle works on pairs)
+    constexpr int RPC = 256 / ROWB;        // rows per 256 bytes = one pass over the 64 LDS banks
     constexpr float TAU = 8.0f;            // lazy-rescale threshold, log2 units
 
     // Two K and two V tile buffers, each TILEB bytes, rows of ROWB bytes, chunk c of row r stored at chunk
-    // c ^ (r % CPR) for K and c ^ (2 * (r % VM)) for V.  They are four separate LDS objects on purpose: the
-    // compiler then knows that a copy in flight into one buffer does not alias reads of the other, and does
-    // not make those reads wait for the copy.
+    // c ^ ((r / RPC) % CPR) for K and c ^ (4 * ((r / RPC) % (CPR / 4))) for V.  The LDS has 64 four-byte banks;
+    // ds_read_b128 serves a wavefront in four passes of 16 lanes (lanes {0-3,12-15,20-27}, {4-11,16-19,28-31} and
+    // the same +32), ds_read_b64_tr_b16 in two passes of 32 lanes, and the swizzles make the 16 (32) addresses of
+    // every pass cover all 64 banks once.  The buffers are four separate LDS objects on purpose: the compiler
+    // then knows that a copy in flight into one buffer does not alias reads of the other, and does not make
+    // those reads wait for the copy.
     __shared__ __attribute__((aligned(1024))) unsigned char sK0[TILEB];
     __shared__ __attribute__((aligned(1024))) unsigned char sK1[TILEB];
     __shared__ __attribute__((aligned(1024))) unsigned char sV0[TILEB];
@@ -113,8 +116,10 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     const unsigned rstride_b = (unsigned)rstride * 2u;
     const int srow = w * RPI + l / CPR;                              // row inside a group of 4*RPI rows
     const int sch = l % CPR;
-    const unsigned voffK = (unsigned)(l / CPR) * rstride_b + (unsigned)((sch ^ (srow % CPR)) * 16);
-    const unsigned voffV = (unsigned)(l / CPR) * rstride_b + (unsigned)((sch ^ (2 * (srow % VM))) * 16);
+    const unsigned swzK = (unsigned)((sch ^ ((srow / RPC) % CPR)) * 16);
+    const unsigned swzV = (unsigned)((sch ^ (4 * ((srow / RPC) % (CPR / 4)))) * 16);
+    const unsigned voffK = (unsigned)(l / CPR) * rstride_b + swzK;
+    const unsigned voffV = (unsigned)(l / CPR) * rstride_b + swzV;
     const unsigned char* const Kg = reinterpret_cast<const unsigned char*>(a.lv.K + (int64_t)kvh * D);
     const unsigned char* const Vg = reinterpret_cast<const unsigned char*>(a.lv.V + (int64_t)kvh * D);
 
@@ -134,8 +139,8 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
             for (int i = 0; i < ROUNDS; ++i) {
                 const int key = min(key0 + i * 4 * RPI + srow, ke - 1);
                 const int64_t ro = (int64_t)key * rstride_b;
-                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Kg + ro + (sch ^ (srow % CPR)) * 16), HG_LDS(kdst + i * (4 * RPI * ROWB)), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Vg + ro + (sch ^ (2 * (srow % VM))) * 16), HG_LDS(vdst + i * (4 * RPI * ROWB)), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Kg + ro + swzK), HG_LDS(kdst + i * (4 * RPI * ROWB)), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(HG_GLOBAL(Vg + ro + swzV), HG_LDS(vdst + i * (4 * RPI * ROWB)), 16, 0, 0);
             }
         }
     };
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     // K operand for k-step s: row = 32*sb + lq, chunk 2s+hl
     unsigned kaddr[KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) kaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    for (int s = 0; s < KS; ++s) kaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ ((lq / RPC) % CPR)) * 16));
     // V^T operand for d-block db: within each 16-lane group, lane i addresses key (i/4) of the 4 keys being
     // transposed and columns dbase + 4*(i%4) .. +3; after the transposing read lane i holds column dbase + i
     // of those 4 keys.  Group (l/16)&1 selects the lower/upper 16 columns, hl the key quad.
@@ -152,7 +157,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     {
         const int i16 = l & 15, g1 = (l >> 4) & 1;
         const int keyq = 4 * hl + (i16 >> 2);                 // key inside an 8-key half step
-        const int fv = 2 * (keyq % VM);
+        const int fv = 4 * ((keyq / RPC) % (CPR / 4));
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);

@@ -31,7 +31,6 @@ constexpr int RPI = 64 / CPR;                // rows one wavefront copies per di
 constexpr int ROUNDS = KT / (NW * RPI);      // such instructions per wavefront per tile and tensor
 constexpr int ROWB = D * 2;                  // bytes per row
 constexpr int TILEB = KT * ROWB;             // bytes per K (or V) tile
-constexpr int VM = CPR / 2;                  // 32-byte chunk pairs per row (V swizzle works on pairs)
 constexpr float TAU = 8.0f;                  // lazy-rescale threshold, log2 units
 static_assert(kPrefixRowsWide == 32 * NW, "one 32-row query block per wavefront");
 
@@ -41,7 +40,8 @@ template <int N> using IC = std::integral_constant<int, N>;
 __global__ __launch_bounds__(64 * NW, 2) void prefix_kernel_wide(PrefixArgs a) {
     // three K and three V tile buffers as separate LDS objects (so that the compiler can tell a copy in flight
     // into one of them from reads of another); rows of ROWB bytes, chunk c of row r at c ^ (r % 16) for K and
-    // c ^ (2 * (r % 8)) for V
+    // c ^ (4 * (r % 4)) for V (conflict free over the 64 banks for the 16-lane passes of ds_read_b128 and the
+    // 32-lane passes of ds_read_b64_tr_b16)
     __shared__ __attribute__((aligned(1024))) unsigned char sK0[TILEB];
     __shared__ __attribute__((aligned(1024))) unsigned char sK1[TILEB];
     __shared__ __attribute__((aligned(1024))) unsigned char sK2[TILEB];
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_kernel_wide(PrefixArgs a) {
     const int srow = w * RPI + l / CPR;                // row inside a group of NW*RPI = 32 rows
     const int sch = l % CPR;
     const unsigned swzK = (unsigned)((sch ^ (srow % CPR)) * 16);
-    const unsigned swzV = (unsigned)((sch ^ (2 * (srow % VM))) * 16);
+    const unsigned swzV = (unsigned)((sch ^ (4 * (srow % 4))) * 16);
     const unsigned voffK = (unsigned)(l / CPR) * rstride_b + swzK;
     const unsigned voffV = (unsigned)(l / CPR) * rstride_b + swzV;
     const unsigned char* const Kg = reinterpret_cast<const unsigned char*>(a.lv.K + (int64_t)kvh * D);
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * NW, 2) void prefix_kernel_wide(PrefixArgs a) {
     {
         const int i16 = l & 15, g1 = (l >> 4) & 1;
         const int keyq = 4 * hl + (i16 >> 2);
-        const int fv = 2 * (keyq % VM);
+        const int fv = 4 * (keyq % 4);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);
