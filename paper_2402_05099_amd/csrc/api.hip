@@ -91,20 +91,29 @@ int pick_gt(int G) {
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
 
-// which shared-block kernel runs a level, and over how many key-range splits
-struct LevelPlan { bool wide; int ns; };
+// which shared-block kernel runs a level, and how many partial results per row it writes
+struct LevelPlan { bool wide; int ns; WidePlan wp; };
 
-// The 128-row kernel (two workgroups per CU, ~200 VGPRs) is the default: it leaves register space on every SIMD
-// for suffix wavefronts to run beside it.  The 256-row kernel (D = 128 only) is selected by option.
-LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D) {
-    LevelPlan p;
-    const int rows = lv.max_seqs * G;
-    p.wide = D == 128 && c->opt_prefix_kernel == 2;
+// The persistent 256-row kernel (D = 128) runs a level whose blocks have more than 128 query rows; the 128-row
+// kernel runs the rest (small blocks would leave most of a 256-row tile empty) and every D = 64 level.
+// HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel wherever D = 128.  max_parts bounds the
+// partial results the plan may use.
+LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D, int max_parts) {
+    LevelPlan p{};
+    const long long rows = (long long)lv.max_seqs * G;
+    p.wide = false;
     p.ns = 1;
     if (lv.max_rows <= 0) return p;
-    const int tile_rows = p.wide ? kPrefixRowsWide : kPrefixRowsNarrow;
-    const int slots = p.wide ? 256 : 512;   // workgroups resident on the 256 CUs
-    const int64_t base = (int64_t)lv.n_blocks * ceil_div(rows, tile_rows) * Hkv;
+    if (max_parts < 1) max_parts = 1;
+    if (max_parts > HG_MAX_PARTS) max_parts = HG_MAX_PARTS;
+    const bool want_wide = D == 128 && c->opt_prefix_kernel != 1 && (c->opt_prefix_kernel == 2 || rows > kPrefixRowsNarrow);
+    if (want_wide && plan_prefix_wide(lv, Hkv, G, max_parts, &p.wp)) {
+        p.wide = true;
+        p.ns = p.wp.nparts;
+        return p;
+    }
+    const int slots = 512;   // 128-row workgroups resident on the 256 CUs (two per CU)
+    const int64_t base = (int64_t)lv.n_blocks * ceil_div((int)rows, kPrefixRowsNarrow) * Hkv;
     const int max_ns = ceil_div(lv.max_rows, kPrefixKeys);
     int ns;
     if (c->opt_prefix_splits > 0) {
@@ -118,6 +127,7 @@ LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D)
         if (ns > 16) ns = 16;
     }
     if (ns > max_ns) ns = max_ns;
+    if (ns > max_parts) ns = max_parts;
     if (ns < 1) ns = 1;
     p.ns = ns;
     return p;
@@ -130,16 +140,20 @@ int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int Hq, 
     a.Q = static_cast<const uint16_t*>(Q);
     a.lv = lv;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
-    a.mtiles = ceil_div(lv.max_seqs * a.G, plan.wide ? kPrefixRowsWide : kPrefixRowsNarrow);
+    a.scale = scale;
+    a.out = out;
+    if (plan.wide) {
+        a.wide = plan.wp;
+        return hip_rc(launch_prefix_wide(a, s));
+    }
+    a.mtiles = ceil_div(lv.max_seqs * a.G, kPrefixRowsNarrow);
     a.nsplit = plan.ns;
     a.chunk = round_up(ceil_div(lv.max_rows > 0 ? lv.max_rows : 1, plan.ns), kPrefixKeys);
     const int64_t total = (int64_t)lv.n_blocks * plan.ns * Hkv * a.mtiles;
     if (total >= (1LL << 28)) return HG_ERR_UNSUPPORTED;
     a.total_tiles = (int)total;
     a.per_xcd = ceil_div(a.total_tiles, 8);
-    a.scale = scale;
-    a.out = out;
-    return hip_rc(plan.wide ? launch_prefix_wide(a, s) : launch_prefix_narrow(a, D, s));
+    return hip_rc(launch_prefix_narrow(a, D, s));
 }
 
 struct SuffixPlan { int chunk, nchunks, gt; };
@@ -313,8 +327,7 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     const int64_t rows = (int64_t)B * Hq;
     const LevelDev lv = to_dev(*level, B);
     const Parts parts = carve(c, rows, D);
-    LevelPlan plan = plan_level(c, lv, Hkv, Hq / Hkv, D);
-    if (plan.ns > parts.cap) plan.ns = parts.cap > 1 ? parts.cap : 1;
+    const LevelPlan plan = plan_level(c, lv, Hkv, Hq / Hkv, D, parts.cap);
     const int ns = plan.ns;
     hipStream_t s = c->stream;
     if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
@@ -432,7 +445,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         LevelDev d = to_dev(levels[i], B);
         if (d.max_rows == 0 || d.max_seqs == 0) continue;  // empty level contributes nothing
         lv[nlev] = d;
-        plan[nlev] = plan_level(c, d, Hkv, G, D);
+        plan[nlev] = plan_level(c, d, Hkv, G, D, parts.cap);
         ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
@@ -448,7 +461,8 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
             sp.chunk = round_up(ceil_div(max_len, sp.nchunks), 32);
             sp.nchunks = ceil_div(max_len, sp.chunk);
         } else if (big >= 0) {
-            ns[big] -= 1;
+            plan[big] = plan_level(c, lv[big], Hkv, G, D, ns[big] - 1);
+            ns[big] = plan[big].ns;
         } else {
             return HG_ERR_WORKSPACE;
         }
@@ -499,7 +513,6 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         int part = 0;
         for (int i = 0; i < nlev; ++i) {
             if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
-            plan[i].ns = ns[i];
             const int r = run_level(Q, lv[i], plan[i], B, Hq, Hkv, D, scale, parts_out(parts, part), s);
             if (r) return r;
             if (!mark(1 + i, 1, s)) return HG_ERR_HIP;

@@ -31,6 +31,17 @@ struct OutDev {
     int64_t part_stride_L;
 };
 
+// Work partition of the persistent 256-row shared-block kernel (prefix_wide.hip).
+struct WidePlan {
+    int n_c;        // 32-key stages per column, from the host's bound on rows per block
+    int ncols;      // columns = n_blocks * Hkv * rowgroups
+    int rowgroups;  // groups of at most 32 query-row tiles
+    int T;          // workgroups per team = query-row tiles per row group
+    int tpx;        // teams per XCD (32 / T)
+    int quota;      // stages per team
+    int nparts;     // partial results per query row
+};
+
 struct PrefixArgs {
     const uint16_t* Q;
     LevelDev lv;
@@ -42,6 +53,7 @@ struct PrefixArgs {
     int per_xcd;      // ceil(total_tiles / 8)
     float scale;      // softmax scale
     OutDev out;       // part index = split
+    WidePlan wide;    // persistent kernel only
 };
 
 struct DecodeArgs {
@@ -76,7 +88,8 @@ struct FillArgs {
 
 // ---- launchers (defined next to their kernels) ------------------------------------------------------
 hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s);
-hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only
+hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only; a.wide from plan_prefix_wide
+bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, WidePlan* out);
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
