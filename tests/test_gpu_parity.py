@@ -137,8 +137,9 @@ def test_grouped_level_with_uncovered_sequences_and_unequal_blocks():
     lv.seq_off = np.array([0, 11, 30, 33], np.int32)      # unequal sequences: 11, 19, 3
     dw = dev.to_device(w)
     ctx = dev.make_context(dw, parts=8)
-    for splits in (1, 2):
+    for splits, kernel in ((1, 0), (2, 0), (0, 2)):   # kernel 2: the persistent 256-row kernel on the same ragged blocks
         ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
+        ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
         Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
         assert np.isneginf(Lref[40]).all()
         O, L, intact = outputs(dw)
@@ -152,6 +153,31 @@ def test_grouped_level_with_uncovered_sequences_and_unequal_blocks():
         O3, L3 = dev.naive(ctx, dw, torch.float32)
         torch.cuda.synchronize()
         check(to_np(O3), to_np(L3), Of, Lf, "uncovered naive")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,P,parts", [
+    ("three_tiles", 75, 8, 1, 1000, 8),      # 600 query rows per KV head: teams of 3 workgroups, ragged last tile and stage
+    ("three_tiles_two_parts", 75, 8, 1, 1000, 2),   # workspace for two partial results only: longer ranges per team
+    ("one_part", 40, 8, 2, 700, 1),          # no workspace for partials: one team per column, direct output
+    ("row_groups", 1030, 8, 1, 100, 8),      # 8240 rows = 33 tiles of 256: two row groups of 17 tiles
+    ("tiny_block", 40, 8, 2, 5, 8),          # fewer keys than one 32-key stage, at the very start of the tensor
+    ("one_stage_plus_one", 33, 8, 1, 33, 8),
+])
+def test_persistent_kernel_partitions(name, B, Hq, Hkv, P, parts):
+    """Work partitions of the persistent 256-row shared-block kernel that the five configs do not reach."""
+    say(f"persistent partitions {name}")
+    w = wl.make_workload(name, 77, B, Hq, Hkv, 128, [(1, P, B)], 0, 0)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=parts)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, 2)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    lv = dw.levels[0]
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"persistent {name} {dtype}", out_bf16=dtype == torch.bfloat16)
     ctx.close()
 
 
