@@ -49,6 +49,7 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--prefix-kernel", type=int, default=0, help="0 auto, 1 128-row workgroups, 2 256-row workgroups")
+    ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -81,6 +82,8 @@ def main() -> int:
         ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, args.suffix_chunk)
     ctx.set_option(hb.HG_OPT_OVERLAP, args.overlap)
     ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, args.prefix_kernel)
+    if args.wide_slots:
+        ctx.set_option(hb.HG_OPT_WIDE_SLOTS, args.wide_slots)
 
     O = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.bfloat16, device="cuda:0")
     L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")

@@ -17,6 +17,7 @@ HG_OK, HG_ERR_INVALID_ARG, HG_ERR_UNSUPPORTED, HG_ERR_WORKSPACE, HG_ERR_HIP = 0,
 HG_F32, HG_BF16 = 0, 1
 HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING, HG_OPT_PREFIX_KERNEL = 1, 2, 3, 4, 5, 6
+HG_OPT_WIDE_SLOTS = 7
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)

@@ -15,6 +15,7 @@ struct hg_ctx {
     int opt_overlap;
     int opt_naive_chunk;
     int opt_prefix_kernel;
+    int opt_wide_slots;
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -98,7 +99,7 @@ struct LevelPlan { bool wide; int ns; WidePlan wp; };
 // kernel runs the rest (small blocks would leave most of a 256-row tile empty) and every D = 64 level.
 // HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel wherever D = 128.  max_parts bounds the
 // partial results the plan may use.
-LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D, int max_parts) {
+LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D, int max_parts, int wide_slots = 32) {
     LevelPlan p{};
     const long long rows = (long long)lv.max_seqs * G;
     p.wide = false;
@@ -107,7 +108,7 @@ LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D,
     if (max_parts < 1) max_parts = 1;
     if (max_parts > HG_MAX_PARTS) max_parts = HG_MAX_PARTS;
     const bool want_wide = D == 128 && c->opt_prefix_kernel != 1 && (c->opt_prefix_kernel == 2 || rows > kPrefixRowsNarrow);
-    if (want_wide && plan_prefix_wide(lv, Hkv, G, max_parts, &p.wp)) {
+    if (want_wide && plan_prefix_wide(lv, Hkv, G, max_parts, c->opt_wide_slots > 0 ? c->opt_wide_slots : wide_slots, &p.wp)) {
         p.wide = true;
         p.ns = p.wp.nparts;
         return p;
@@ -215,6 +216,40 @@ OutDev parts_out(const Parts& p, int first) {
     return o;
 }
 
+// CUs per XCD for the persistent shared-block kernel when it overlaps the suffix kernel in the fused call.
+// The shared-block kernel runs against the chip's power limit, so it loses little on fewer CUs (measured on
+// config 3: 0.96 / 0.90 / 0.82 / 0.69 / 0.54 of its full-chip rate on 28 / 24 / 20 / 16 / 12 CUs per XCD), while
+// the memory-bound suffix kernel takes the CUs that are left.  Model: while the shared-block kernel runs the
+// suffix kernel streams at 0.7 x 6 TB/s x (its share of the CUs) (measured 0.92 / 1.77 / 2.06 TB/s on 64 / 96 /
+// 128 CUs), afterwards at 6 TB/s; pick the count with the smallest finish time.  flops: shared-block work; bytes: suffix KV traffic (estimated from max_len).
+int pick_wide_slots(double flops, double bytes, int T) {
+    // relative rate of the shared-block kernel on 4, 8, .., 32 CUs per XCD (measured down to 12, scaled below)
+    static const double rate[] = {0.18, 0.36, 0.543, 0.693, 0.823, 0.895, 0.964, 1.0};
+    const double full_rate = 1.14e15, bw = 6.0e12;
+    if (T < 1) T = 1;
+    auto rate_at = [&](int eff) { return rate[eff / 4 - 1] + (rate[(eff + 3) / 4 - 1] - rate[eff / 4 - 1]) * (eff % 4) / 4.0; };
+    const double ts = bytes / bw, tp32 = flops / full_rate;
+    if (ts >= 2.0 * tp32) {
+        // the suffix kernel dominates: the fewest CUs on which the shared blocks still finish in half its time
+        for (int s = 4; s <= 32; s += 4) {
+            const int eff = s / T * T;
+            if (eff >= 4 && flops / (full_rate * rate_at(eff)) <= 0.5 * ts) return s;
+        }
+        return 32;
+    }
+    int best = 32;
+    double best_t = 1e30;
+    for (int s = 32; s >= 4; s -= 4) {
+        const int eff = s / T * T;                 // CUs per XCD that hold whole teams; the others are released at once
+        if (eff < 4) break;
+        const double tp = flops / (full_rate * rate_at(eff));
+        const double conc = 0.7 * bw * (256 - 8 * eff) / 256.0;
+        const double t = bytes <= conc * tp ? tp : tp + (bytes - conc * tp) / bw;
+        if (t < best_t * 0.98) { best_t = t; best = s; }
+    }
+    return best;
+}
+
 int fill_empty(void* O, int o_dtype, float* LSE, int64_t rows, int D, hipStream_t s) {
     FillArgs f{};
     f.O = O; f.LSE = LSE; f.bf16 = (o_dtype == HG_BF16); f.rows = rows; f.D = D;
@@ -239,7 +274,7 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->ws = static_cast<unsigned char*>(workspace);
     c->ws_bytes = workspace_bytes;
-    c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = c->opt_prefix_kernel = 0;
+    c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = c->opt_prefix_kernel = c->opt_wide_slots = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -289,6 +324,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_PREFIX_KERNEL:
             if (value > 2) return HG_ERR_INVALID_ARG;
             c->opt_prefix_kernel = value;
+            return HG_OK;
+        case HG_OPT_WIDE_SLOTS:
+            if (value > 32) return HG_ERR_INVALID_ARG;
+            c->opt_wide_slots = value;
             return HG_OK;
         case HG_OPT_STAGE_TIMING:
             if (value && !c->tev) {
@@ -441,11 +480,24 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
     LevelPlan plan[HG_MAX_LEVELS];
     int ns[HG_MAX_LEVELS];
     int nlev = 0;
+    int wide_slots = 32;
+    if (has_suffix && c->opt_overlap != 1) {
+        double flops = 0.0;
+        int T = 1;
+        for (int i = 0; i < n_levels; ++i) {
+            const long long seqs = levels[i].kv_off ? levels[i].max_seqs : B;
+            flops += 4.0 * levels[i].n_blocks * (double)levels[i].max_rows * seqs * Hq * D;
+            const long long tiles = (seqs * G + kPrefixRowsWide - 1) / kPrefixRowsWide;
+            if (seqs * G > kPrefixRowsNarrow && tiles <= 32 && tiles > T) T = (int)tiles;
+        }
+        const double bytes = 4.0 * B * (0.75 * max_len) * Hkv * D;   // K and V, bf16; mean length taken as 0.75 max_len
+        wide_slots = pick_wide_slots(flops, bytes, T);
+    }
     for (int i = 0; i < n_levels; ++i) {
         LevelDev d = to_dev(levels[i], B);
         if (d.max_rows == 0 || d.max_seqs == 0) continue;  // empty level contributes nothing
         lv[nlev] = d;
-        plan[nlev] = plan_level(c, d, Hkv, G, D, parts.cap);
+        plan[nlev] = plan_level(c, d, Hkv, G, D, parts.cap, wide_slots);
         ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
@@ -461,7 +513,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
             sp.chunk = round_up(ceil_div(max_len, sp.nchunks), 32);
             sp.nchunks = ceil_div(max_len, sp.chunk);
         } else if (big >= 0) {
-            plan[big] = plan_level(c, lv[big], Hkv, G, D, ns[big] - 1);
+            plan[big] = plan_level(c, lv[big], Hkv, G, D, ns[big] - 1, wide_slots);
             ns[big] = plan[big].ns;
         } else {
             return HG_ERR_WORKSPACE;
@@ -481,7 +533,11 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         first += ns[i];
     }
 
-    const bool overlap = c->opt_overlap != 1 && has_suffix && nlev > 0;   // 0 automatic = two streams
+    // Two streams unless asked for one.  In automatic mode a call whose levels all run in the persistent kernel on
+    // the whole chip stays on one stream: there is no CU left for the suffix kernel to run beside it.
+    bool all_wide_full = nlev > 0;
+    for (int i = 0; i < nlev; ++i) all_wide_full = all_wide_full && plan[i].wide && plan[i].wp.slots == 32;
+    const bool overlap = c->opt_overlap != 1 && has_suffix && nlev > 0 && !(c->opt_overlap == 0 && all_wide_full);
     hipStream_t ssfx = s;
     if (overlap) {
         if (hipEventRecord(c->ev_fork, s) != hipSuccess) return HG_ERR_HIP;
@@ -520,10 +576,13 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         }
         return HG_OK;
     };
-    // HG_OPT_OVERLAP 2 enqueues the shared-block kernels before the suffix kernel; otherwise the suffix kernel goes
-    // first.  Either way the memory-bound suffix wavefronts and the matrix-bound shared-block workgroups share the
-    // CUs (the latter leave register space for the former on every SIMD).
-    if (c->opt_overlap == 2) {
+    // Two streams: the memory-bound suffix kernel and the power-bound shared-block kernels run side by side.  The
+    // persistent 256-row kernel takes whole CUs (wide_slots per XCD, chosen above) and is enqueued first so that
+    // its workgroups are placed before the suffix kernel fills the chip; 128-row workgroups leave register space
+    // for suffix wavefronts on their CUs and go second unless HG_OPT_OVERLAP = 2 asks for them first.
+    bool any_wide = false;
+    for (int i = 0; i < nlev; ++i) any_wide = any_wide || plan[i].wide;
+    if (c->opt_overlap == 2 || (c->opt_overlap == 0 && any_wide)) {
         rc = enqueue_levels();
         if (rc) return rc;
         rc = enqueue_suffix();

@@ -37,7 +37,8 @@ struct WidePlan {
     int ncols;      // columns = n_blocks * Hkv * rowgroups
     int rowgroups;  // groups of at most 32 query-row tiles
     int T;          // workgroups per team = query-row tiles per row group
-    int tpx;        // teams per XCD (32 / T)
+    int slots;      // workgroups (CUs) per XCD that the kernel occupies
+    int tpx;        // teams per XCD (slots / T)
     int quota;      // stages per team
     int nparts;     // partial results per query row
 };
@@ -89,7 +90,7 @@ struct FillArgs {
 // ---- launchers (defined next to their kernels) ------------------------------------------------------
 hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s);
 hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only; a.wide from plan_prefix_wide
-bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, WidePlan* out);
+bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slots_per_xcd, WidePlan* out);
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);

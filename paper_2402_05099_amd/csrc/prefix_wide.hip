@@ -367,14 +367,16 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
 
 // Work partition of the persistent kernel for a level (host side).  Returns false when the level does not fit
 // (more than max_parts partial results per row would be needed).
-bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, WidePlan* out) {
+bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slots_per_xcd, WidePlan* out) {
     WidePlan p{};
     const long long rows = (long long)lv.max_seqs * G;
     const int mtiles = (int)((rows + kPrefixRowsWide - 1) / kPrefixRowsWide);
     if (mtiles < 1 || lv.max_rows < 1) return false;
-    p.rowgroups = (mtiles + 31) / 32;                       // at most 32 workgroups of one XCD form a team
+    if (slots_per_xcd < 1 || slots_per_xcd > 32) return false;
+    p.slots = slots_per_xcd;
+    p.rowgroups = (mtiles + p.slots - 1) / p.slots;         // the workgroups of a team run on one XCD
     p.T = (mtiles + p.rowgroups - 1) / p.rowgroups;
-    p.tpx = 32 / p.T;
+    p.tpx = p.slots / p.T;
     p.n_c = (lv.max_rows + KT - 1) / KT;
     const long long ncols = (long long)lv.n_blocks * Hkv * p.rowgroups;
     if (ncols >= (1LL << 24)) return false;
@@ -419,7 +421,7 @@ hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
     }
-    prefix_kernel_wide<<<256, 64 * NW, LDS_BYTES, s>>>(a);
+    prefix_kernel_wide<<<8 * a.wide.slots, 64 * NW, LDS_BYTES, s>>>(a);
     return hipGetLastError();
 }
 

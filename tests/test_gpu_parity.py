@@ -203,18 +203,15 @@ def test_fused_hydragen_and_naive(idx, variant, kernel):
     hb.hg_naive_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
     assert intact()
     check(to_np(O), to_np(L), Oref, Lref, f"naive idx={idx} {variant}")
-    # the single-stream and the other two-stream variant of the fused call give the same bits as the default
-    ctx.set_option(hb.HG_OPT_OVERLAP, 2)
-    O3, L3 = dev.hydragen(ctx, dw, torch.float32)
-    ctx.set_option(hb.HG_OPT_OVERLAP, 1)
-    O2, L2 = dev.hydragen(ctx, dw, torch.float32)
-    torch.cuda.synchronize()
-    assert torch.equal(O3, O2) and torch.equal(L3, L2)
-    O1, L1 = outputs(dw, torch.float32)[:2]
-    ctx.set_option(hb.HG_OPT_OVERLAP, 0)
-    hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O1, L1, dw.scale)
-    torch.cuda.synchronize()
-    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    # every stream arrangement of the fused call meets the same bar (the key ranges of the partial results may
+    # differ between them, so the bits may), and each is deterministic
+    for mode in (2, 1, 0):
+        ctx.set_option(hb.HG_OPT_OVERLAP, mode)
+        Oa, La = dev.hydragen(ctx, dw, torch.float32)
+        Ob, Lb = dev.hydragen(ctx, dw, torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(Oa), to_np(La), Oref, Lref, f"hydragen idx={idx} {variant} overlap={mode}")
+        assert torch.equal(Oa, Ob) and torch.equal(La, Lb)
     ctx.close()
 
 
