@@ -25,11 +25,11 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/fused_c3_P16384_hbm_traffic.txt),
-# each counter scaled by its reading for a 1 GiB device copy (FETCH_SIZE reads 0.50003 of the true KiB on this
+# each counter scaled by its reading for a 1 GiB device copy (FETCH_SIZE reads 0.50002 of the true KiB on this
 # chip, WRITE_SIZE 1.0), keyed by (kernel, workload); None for pairs not measured.
 MEASURED_TRAFFIC = {
-    ("prefix_level0", "c3_long_P16384"): int((184594.3 / 0.50003 + 83430.6) * 1024),
-    ("suffix", "c3_long_P16384"): int((834118.2 / 0.50003 + 20803.0) * 1024),
+    ("prefix_level0", "c3_long_P16384"): int((173540.0 / 0.50002 + 51880.4) * 1024),
+    ("suffix", "c3_long_P16384"): int((834136.4 / 0.50002 + 20804.8) * 1024),
 }
 
 
