@@ -38,7 +38,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload index 1..5 (default: the headline config 3)")
+    ap.add_argument("--config", type=int, default=3, help="workload index 1..6 (default: the headline config 3; 6 = the paper's microbenchmark shape)")
+    ap.add_argument("--batch", type=int, default=0, help="config 6: batch size")
+    ap.add_argument("--suffix-len", type=int, default=0, help="config 6: suffix length of every sequence")
     ap.add_argument("--prefix", type=int, default=0, help="override the level-0 prefix length")
     ap.add_argument("--naive-steps", type=int, default=3)
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences the CPU oracle is timed on (0 = skip)")
@@ -69,7 +71,7 @@ def main() -> int:
     hb.lib()  # fail loudly if the HIP library is missing
 
     t0 = time.time()
-    w = wl.config(args.config, P=args.prefix or None)
+    w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None)
     dw = dev.to_device(w)
     torch.cuda.synchronize()
     print(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} levels={[int(l.K.shape[0]) for l in w.levels]} "

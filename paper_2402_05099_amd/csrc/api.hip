@@ -159,10 +159,19 @@ int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int Hq, 
 
 struct SuffixPlan { int chunk, nchunks, gt; };
 
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G) {
+// Work items of the suffix kernel are (sequence, KV head, group of query heads, key chunk), one wavefront each.
+// 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
+// the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv) {
     SuffixPlan p;
     p.gt = pick_gt(G);
-    p.chunk = c->opt_suffix_chunk > 0 ? round_up(c->opt_suffix_chunk, 32) : 256;
+    if (c->opt_suffix_chunk > 0) {
+        p.chunk = round_up(c->opt_suffix_chunk, 32);
+    } else {
+        p.chunk = 256;
+        const long long per_chunk = (long long)B * Hkv * (G / p.gt);
+        while (p.chunk > 64 && per_chunk * ceil_div(max_len > 0 ? max_len : 1, p.chunk) < 2048) p.chunk /= 2;
+    }
     p.nchunks = max_len > 0 ? ceil_div(max_len, p.chunk) : 1;
     return p;
 }
@@ -409,7 +418,7 @@ int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, con
     hipStream_t s = c->stream;
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, Hkv);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
@@ -501,7 +510,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
-    SuffixPlan sp = plan_suffix(c, max_len, G);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B, Hkv);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;

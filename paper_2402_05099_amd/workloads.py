@@ -220,8 +220,12 @@ def make_workload(
 
 
 # The five benchmark configurations (index 1..5), each with its fixed seed.
-def config(idx: int, P: Optional[int] = None, **variant) -> Workload:
-    """idx in 1..5.  `P` overrides the level-0 prefix length (config 3 sweeps 1024/4096/16384)."""
+def config(idx: int, P: Optional[int] = None, B: Optional[int] = None, L: Optional[int] = None, **variant) -> Workload:
+    """idx in 1..6.  `P` overrides the level-0 prefix length (config 3 sweeps 1024/4096/16384).
+
+    6 is the shape of the paper's attention microbenchmark (Sec. 4.2: eight query heads, one KV head, head
+    dimension 128), swept over batch size `B`, prefix length `P` and suffix length `L` (every sequence has L rows).
+    """
     if idx == 1:
         return make_workload("c1_tiny", 1, 4, 4, 4, 64, [(1, P or 128, 4)], 16, 16, **variant)
     if idx == 2:
@@ -233,6 +237,9 @@ def config(idx: int, P: Optional[int] = None, **variant) -> Workload:
         return make_workload("c4_gqa", 4, 512, 64, 8, 128, [(1, P or 4096, 512)], 1, 512, **variant)
     if idx == 5:
         return make_workload("c5_tree", 5, 2048, 40, 40, 128, [(1, P or 1024, 2048), (16, 512, 128)], 64, 64, **variant)
+    if idx == 6:
+        b, p, l = B or 1024, P or 16384, L or 128
+        return make_workload(f"c6_micro_B{b}_P{p}_L{l}", 6, b, 8, 1, 128, [(1, p, b)], l, l, **variant)
     raise ValueError(f"no config {idx}")
 
 
@@ -251,4 +258,6 @@ def scaled_down(idx: int, **variant) -> Workload:
         return make_workload("c4_small", 14, 45, 16, 2, 128, [(1, 515, 45)], 1, 150, **variant)
     if idx == 5:
         return make_workload("c5_small", 15, 96, 4, 4, 128, [(1, 200, 96), (4, 77, 24)], 20, 20, **variant)
+    if idx == 6:
+        return make_workload("c6_small", 16, 75, 8, 1, 128, [(1, 700, 75)], 50, 50, **variant)
     return config(1, **variant)

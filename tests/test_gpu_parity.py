@@ -184,7 +184,7 @@ def test_persistent_kernel_partitions(name, B, Hq, Hkv, P, parts):
 VARIANTS = [dict(), dict(q_gain=4.0), dict(plant="suffix"), dict(plant="prefix")]
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("variant", VARIANTS, ids=["normal", "peaked", "plant_suffix", "plant_prefix"])
 @pytest.mark.parametrize("kernel", [0, 2], ids=["auto", "rows256"])
 def test_fused_hydragen_and_naive(idx, variant, kernel):

@@ -223,7 +223,7 @@ def library_attention(w, b):
     return np.einsum("hn,nhd->hd", Pm, V), scipy.special.logsumexp(S, axis=1)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 def test_library_softmax_on_scaled_down_configs(idx):
     """covers MHA, ragged suffixes, GQA-by-repetition (idx 4) and the tree by physical concatenation (idx 5)"""
     w = wl.scaled_down(idx)
