@@ -33,8 +33,18 @@
  *     LSE = -inf.  (The paper is silent on empty parts.)
  *   - No causal mask: the decode query attends to every listed key
  *     (its own K/V row is expected to be the last suffix row already).
+ *   - Several queries per sequence (App. B's num_queries > 1: the last nq tokens
+ *     of every sequence are queried at once, as when draft tokens are verified).
+ *     hg_set_option(ctx, HG_OPT_NUM_QUERIES, nq) makes every call of the context
+ *     read Q as bf16 [B, nq, Hq, D] and write O [B, nq, Hq, D], LSE [B, nq, Hq];
+ *     B stays the number of sequences in shapes, offsets, lengths and seq_off.
+ *     Query t (0-based) of sequence b attends to every row of the shared blocks
+ *     that cover b and to suffix rows [0, lengths[b] - (nq-1-t)): the nq tokens
+ *     are the last nq suffix rows and a token does not see the ones after it
+ *     (the paper gives the shape only; the causal reading is this library's).
+ *     hg_merge is unaffected (it takes a row count).
  *   - scale <= 0 selects 1/sqrt(D) (Eq. 1).
- *   - Supported: D in {64, 128}; Hq % Hkv == 0; B*Hq*D < 2^31; rows*Hkv*D < 2^31 per tensor.
+ *   - Supported: D in {64, 128}; Hq % Hkv == 0; B*nq*Hq*D < 2^31; rows*Hkv*D < 2^31 per tensor.
  *   - Every call returns HG_OK or an error code; on error nothing is enqueued
  *     and outputs are untouched.  No C++ exception crosses this boundary.
  *   - Calls on one context must not overlap in time from several host threads.
@@ -63,7 +73,8 @@ enum {
     HG_OPT_NAIVE_CHUNK = 4,   /* keys per work item of the non-decomposed comparison kernel */
     HG_OPT_STAGE_TIMING = 5,  /* 1: hg_hydragen_attn brackets each of its kernels with timing events */
     HG_OPT_PREFIX_KERNEL = 6, /* shared-block kernel: 0 automatic (persistent 256-row kernel for D = 128 blocks with more than 128 query rows, else the 128-row kernel), 1 always 128-row, 2 256-row wherever D = 128 */
-    HG_OPT_WIDE_SLOTS = 7     /* CUs per XCD (1..32) that the persistent 256-row kernel occupies; 0 = default */
+    HG_OPT_WIDE_SLOTS = 7,    /* CUs per XCD (1..32) that the persistent 256-row kernel occupies; 0 = automatic */
+    HG_OPT_NUM_QUERIES = 8    /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
 };
 enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };
 

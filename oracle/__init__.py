@@ -65,12 +65,18 @@ def attention_arrays(
 ):
     """Exact attention over (shared blocks covering b) || (suffix of b) for each sequence.
 
-    Q: uint16 [B,Hq,D]; levels: list of (K, V, kv_off, seq_off); suffix arrays optional.
-    Returns (O float64 [n,Hq,D], LSE float64 [n,Hq]) for the n selected sequences.
+    Q: uint16 [B,Hq,D], or [B,nq,Hq,D] for nq queries per sequence (query t sees suffix rows
+    [0, length - (nq-1-t))); levels: list of (K, V, kv_off, seq_off); suffix arrays optional.
+    Returns (O float64 [n,Hq,D], LSE float64 [n,Hq]) for the n selected sequences ([n,nq,Hq,D] and [n,nq,Hq] for 4-d Q).
     """
     lib = _load()
     Q = _u16(Q)
-    B, Hq, D = Q.shape
+    four = Q.ndim == 4
+    if four:
+        B, nq, Hq, D = Q.shape
+    else:
+        B, Hq, D = Q.shape
+        nq = 1
     if scale is None:
         scale = 1.0 / np.sqrt(D)
     nl = len(levels)
@@ -101,10 +107,10 @@ def attention_arrays(
         n = int(seqs.shape[0])
     else:
         n = B
-    O = np.empty((n, Hq, D), dtype=np.float64)
-    LSE = np.empty((n, Hq), dtype=np.float64)
+    O = np.empty((n, nq, Hq, D) if four else (n, Hq, D), dtype=np.float64)
+    LSE = np.empty((n, nq, Hq) if four else (n, Hq), dtype=np.float64)
     rc = lib.hgo_attention(
-        _ptr(Q), B, Hq, Hkv, D, nl, Kp, Vp, _ptr(Gn), kop, sop,
+        _ptr(Q), B, nq, Hq, Hkv, D, nl, Kp, Vp, _ptr(Gn), kop, sop,
         _ptr(Ks), _ptr(Vs), _ptr(offsets), _ptr(lengths), ctypes.c_double(float(scale)),
         _ptr(seqs), n, _ptr(O), _ptr(LSE),
     )

@@ -16,6 +16,11 @@
  *                  concatenated cache is the ground truth; Sec. 3.3 for trees)
  *                  followed by b's own suffix rows, together with the
  *                  log-sum-exp of the scaled scores (Eq. 4, natural log).
+ *                  With nq > 1 queries per sequence (App. B's num_queries:
+ *                  the last nq tokens of a sequence queried at once) query t
+ *                  sees every shared row and suffix rows [0, L_b - (nq-1-t)):
+ *                  the plain causal definition, a token does not see the
+ *                  tokens after it (the paper gives only the shape).
  *                  With zero levels it is attention over the suffix alone;
  *                  with all lengths zero it is attention over shared blocks
  *                  alone: those give the per-part (O, LSE) pairs.
@@ -94,19 +99,19 @@ static void attend(const double *q, int D, int Hkv, int kvh, const span_t *spans
 #define HGO_MAX_LEVELS 8
 
 /*
- * Q [B,Hq,D] bf16 bits.  Level l: K/V [rows_l,Hkv,D], Gn[l] blocks, kv_off[l][Gn+1], seq_off[l][Gn+1].
+ * Q [B,nq,Hq,D] bf16 bits (nq >= 1 queries per sequence).  Level l: K/V [rows_l,Hkv,D], Gn[l] blocks, kv_off[l][Gn+1], seq_off[l][Gn+1].
  * Suffix: Ks/Vs [T,Hkv,D], offsets[B], lengths[B] (Ks may be NULL when every length is 0 or lengths is NULL).
  * seqs: optional list of n_seqs sequence ids to evaluate (NULL = all B, n_seqs ignored).
- * Outputs are indexed by position in that list: O [n,Hq,D], LSE [n,Hq], fp64.
+ * Outputs are indexed by position in that list: O [n,nq,Hq,D], LSE [n,nq,Hq], fp64.
  * Returns 0, or -1 on a bad argument.
  */
-int hgo_attention(const uint16_t *Q, int B, int Hq, int Hkv, int D,
+int hgo_attention(const uint16_t *Q, int B, int nq, int Hq, int Hkv, int D,
                   int n_levels, const uint16_t *const *Kl, const uint16_t *const *Vl,
                   const int32_t *Gn, const int32_t *const *kv_off, const int32_t *const *seq_off,
                   const uint16_t *Ks, const uint16_t *Vs, const int32_t *offsets, const int32_t *lengths,
                   double scale, const int32_t *seqs, int n_seqs, double *O, double *LSE)
 {
-    if (B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -1;
+    if (B < 0 || nq < 1 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0) return -1;
     if (n_levels < 0 || n_levels > HGO_MAX_LEVELS) return -1;
     const int G = Hq / Hkv;
     const int n = seqs ? n_seqs : B;
@@ -141,24 +146,30 @@ int hgo_attention(const uint16_t *Q, int B, int Hq, int Hkv, int D,
                     }
                 }
             }
-            if (lengths && lengths[b] > 0) {
-                spans[ns].K = Ks;
-                spans[ns].V = Vs;
-                spans[ns].begin = offsets[b];
-                spans[ns].count = lengths[b];
-                total += spans[ns].count;
-                ++ns;
-            }
-            if (total > cap) {
+            const int nshared = ns;
+            const int64_t len_b = lengths && lengths[b] > 0 ? lengths[b] : 0;
+            if (total + len_b > cap) {
                 free(scores);
-                cap = total;
+                cap = total + len_b;
                 scores = (double *)malloc(sizeof(double) * (size_t)cap);
             }
-            for (int h = 0; h < Hq; ++h) {
-                const uint16_t *qb = Q + ((int64_t)b * Hq + h) * D;
-                for (int d = 0; d < D; ++d) q[d] = widen(qb[d]);
-                attend(q, D, Hkv, h / G, spans, ns, scale, scores,
-                       O + ((int64_t)i * Hq + h) * D, LSE + (int64_t)i * Hq + h);
+            for (int t = 0; t < nq; ++t) {
+                /* query t is the (nq-1-t)-th token from the end: it sees the suffix up to and including itself */
+                const int64_t visible = len_b - (nq - 1 - t);
+                ns = nshared;
+                if (visible > 0) {
+                    spans[ns].K = Ks;
+                    spans[ns].V = Vs;
+                    spans[ns].begin = offsets[b];
+                    spans[ns].count = visible;
+                    ++ns;
+                }
+                for (int h = 0; h < Hq; ++h) {
+                    const uint16_t *qb = Q + (((int64_t)b * nq + t) * Hq + h) * D;
+                    for (int d = 0; d < D; ++d) q[d] = widen(qb[d]);
+                    attend(q, D, Hkv, h / G, spans, ns, scale, scores,
+                           O + (((int64_t)i * nq + t) * Hq + h) * D, LSE + ((int64_t)i * nq + t) * Hq + h);
+                }
             }
         }
         free(scores);

@@ -18,6 +18,7 @@ HG_F32, HG_BF16 = 0, 1
 HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING, HG_OPT_PREFIX_KERNEL = 1, 2, 3, 4, 5, 6
 HG_OPT_WIDE_SLOTS = 7
+HG_OPT_NUM_QUERIES = 8
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)
@@ -184,31 +185,46 @@ class Context:
             pass
 
 
+def _qshape(ctx: Context, Q):
+    """(B, Hq, D, output leading shape) of Q [B,Hq,D] or [B,nq,Hq,D]; tells the context how many queries a sequence has."""
+    if Q.ndim == 4:
+        B, nq, Hq, D = Q.shape
+        lead = (B, nq, Hq)
+    else:
+        B, Hq, D = Q.shape
+        nq = 1
+        lead = (B, Hq)
+    if getattr(ctx, "_nq", 1) != nq:
+        ctx.set_option(HG_OPT_NUM_QUERIES, nq)
+        ctx._nq = nq
+    return B, Hq, D, lead
+
+
 def hg_prefix_attn(ctx: Context, Q, Kp, Vp, O, LSE, scale: float = 0.0) -> None:
-    B, Hq, D = Q.shape
+    B, Hq, D, lead = _qshape(ctx, Q)
     P, Hkv, _ = Kp.shape
     _want(Q, torch.bfloat16, name="Q"); _want(Kp, torch.bfloat16, (P, Hkv, D), "Kp"); _want(Vp, torch.bfloat16, (P, Hkv, D), "Vp")
-    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    _want(O, O.dtype, lead + (D,), "O"); _want(LSE, torch.float32, lead, "LSE")
     _check(lib().hg_prefix_attn(ctx.h, _p(Q), _p(Kp), _p(Vp), B, Hq, Hkv, D, P, scale, _p(O), _dtype_code(O), _p(LSE)),
            "hg_prefix_attn")
 
 
 def hg_prefix_attn_grouped(ctx: Context, Q, level: Level, O, LSE, scale: float = 0.0) -> None:
-    B, Hq, D = Q.shape
+    B, Hq, D, lead = _qshape(ctx, Q)
     Hkv = level.K.shape[1]
     _want(Q, torch.bfloat16, name="Q"); _want(level.K, torch.bfloat16, name="K"); _want(level.V, torch.bfloat16, level.K.shape, "V")
-    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    _want(O, O.dtype, lead + (D,), "O"); _want(LSE, torch.float32, lead, "LSE")
     st = level.c_struct()
     _check(lib().hg_prefix_attn_grouped(ctx.h, _p(Q), ctypes.byref(st), B, Hq, Hkv, D, scale, _p(O), _dtype_code(O), _p(LSE)),
            "hg_prefix_attn_grouped")
 
 
 def hg_suffix_attn(ctx: Context, Q, Ks, Vs, offsets, lengths, max_len: int, O, LSE, scale: float = 0.0) -> None:
-    B, Hq, D = Q.shape
+    B, Hq, D, lead = _qshape(ctx, Q)
     Hkv = Ks.shape[1]
     _want(Q, torch.bfloat16, name="Q"); _want(Ks, torch.bfloat16, name="Ks"); _want(Vs, torch.bfloat16, Ks.shape, "Vs")
     _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
-    _want(O, O.dtype, (B, Hq, D), "O"); _want(LSE, torch.float32, (B, Hq), "LSE")
+    _want(O, O.dtype, lead + (D,), "O"); _want(LSE, torch.float32, lead, "LSE")
     _check(lib().hg_suffix_attn(ctx.h, _p(Q), _p(Ks), _p(Vs), _p(offsets), _p(lengths), max_len, B, Hq, Hkv, D, scale,
                                 _p(O), _dtype_code(O), _p(LSE)), "hg_suffix_attn")
 
@@ -229,7 +245,7 @@ def hg_merge(ctx: Context, O_parts: Sequence[torch.Tensor], LSE_parts: Sequence[
 
 
 def _fused(fn, name, ctx, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale):
-    B, Hq, D = Q.shape
+    B, Hq, D, lead = _qshape(ctx, Q)
     _want(Q, torch.bfloat16, name="Q")
     if levels:
         Hkv = levels[0].K.shape[1]
@@ -242,9 +258,9 @@ def _fused(fn, name, ctx, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_
     if Ks is not None:
         _want(Ks, torch.bfloat16, name="Ks"); _want(Vs, torch.bfloat16, Ks.shape, "Vs")
         _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
-    _want(O_out, O_out.dtype, (B, Hq, D), "O_out")
+    _want(O_out, O_out.dtype, lead + (D,), "O_out")
     if LSE_out is not None:
-        _want(LSE_out, torch.float32, (B, Hq), "LSE_out")
+        _want(LSE_out, torch.float32, lead, "LSE_out")
     n = len(levels)
     arr = (hg_level * max(n, 1))(*[lv.c_struct() for lv in levels])
     _check(fn(ctx.h, _p(Q), n, arr, _p(Ks), _p(Vs), _p(offsets), _p(lengths), max_len, B, Hq, Hkv, D, scale,

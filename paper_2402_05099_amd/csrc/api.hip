@@ -16,6 +16,7 @@ struct hg_ctx {
     int opt_naive_chunk;
     int opt_prefix_kernel;
     int opt_wide_slots;
+    int opt_nq;            // queries per sequence (1 = decode)
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -55,11 +56,11 @@ Parts carve(const hg_ctx* c, int64_t rows, int D) {
     return p;
 }
 
-int check_shape(int B, int Hq, int Hkv, int D) {
-    if (B < 0 || Hq <= 0 || Hkv <= 0) return HG_ERR_INVALID_ARG;
+int check_shape(int B, int Hq, int Hkv, int D, int nq) {
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || nq < 1) return HG_ERR_INVALID_ARG;
     if (D != 64 && D != 128) return HG_ERR_UNSUPPORTED;
     if (Hq % Hkv != 0) return HG_ERR_UNSUPPORTED;
-    if ((int64_t)B * Hq * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    if ((int64_t)B * nq * Hq * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
     return HG_OK;
 }
 
@@ -99,6 +100,7 @@ struct LevelPlan { bool wide; int ns; WidePlan wp; };
 // kernel runs the rest (small blocks would leave most of a 256-row tile empty) and every D = 64 level.
 // HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel wherever D = 128.  max_parts bounds the
 // partial results the plan may use.
+// G: query rows per sequence and KV head (queries per sequence x query heads per KV head).
 LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D, int max_parts, int wide_slots = 32) {
     LevelPlan p{};
     const long long rows = (long long)lv.max_seqs * G;
@@ -135,19 +137,20 @@ LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D,
 }
 
 // enqueue the shared-block kernel for one level with `ns` splits writing to `out` (part = split)
-int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int Hq, int Hkv, int D, float scale,
+int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int nq, int Hq, int Hkv, int D, float scale,
               const OutDev& out, hipStream_t s) {
     PrefixArgs a{};
     a.Q = static_cast<const uint16_t*>(Q);
     a.lv = lv;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
+    a.nq = nq;
     a.scale = scale;
     a.out = out;
     if (plan.wide) {
         a.wide = plan.wp;
         return hip_rc(launch_prefix_wide(a, s));
     }
-    a.mtiles = ceil_div(lv.max_seqs * a.G, kPrefixRowsNarrow);
+    a.mtiles = ceil_div(lv.max_seqs * a.G * nq, kPrefixRowsNarrow);
     a.nsplit = plan.ns;
     a.chunk = round_up(ceil_div(lv.max_rows > 0 ? lv.max_rows : 1, plan.ns), kPrefixKeys);
     const int64_t total = (int64_t)lv.n_blocks * plan.ns * Hkv * a.mtiles;
@@ -177,7 +180,7 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv) {
 }
 
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
-               const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
+               const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
                int gt, const OutDev& out, hipStream_t s) {
     DecodeArgs a{};
     a.Q = static_cast<const uint16_t*>(Q);
@@ -189,9 +192,10 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
     a.lengths = lengths;
     a.max_len = max_len;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.G = Hq / Hkv;
+    a.nq = nq;
     a.chunk = chunk;
     a.nchunks = nchunks;
-    a.units = (int64_t)B * nchunks * Hkv * (a.G / gt);
+    a.units = (int64_t)B * nq * nchunks * Hkv * (a.G / gt);
     a.scale = scale;
     a.out = out;
     return hip_rc(launch_decode(a, D, gt, s));
@@ -284,6 +288,7 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->ws = static_cast<unsigned char*>(workspace);
     c->ws_bytes = workspace_bytes;
     c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = c->opt_prefix_kernel = c->opt_wide_slots = 0;
+    c->opt_nq = 1;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -334,6 +339,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
             if (value > 2) return HG_ERR_INVALID_ARG;
             c->opt_prefix_kernel = value;
             return HG_OK;
+        case HG_OPT_NUM_QUERIES:
+            if (value < 1 || value > 64) return HG_ERR_INVALID_ARG;
+            c->opt_nq = value;
+            return HG_OK;
         case HG_OPT_WIDE_SLOTS:
             if (value > 32) return HG_ERR_INVALID_ARG;
             c->opt_wide_slots = value;
@@ -364,7 +373,7 @@ size_t hg_workspace_bytes(int B, int Hq, int D, int parts) {
 int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int B, int Hq, int Hkv, int D, float scale,
                            void* O, int o_dtype, float* LSE) {
     if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16)) return HG_ERR_INVALID_ARG;
-    int rc = check_shape(B, Hq, Hkv, D);
+    int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
     rc = check_level(level, Hkv, D);
     if (rc) return rc;
@@ -372,10 +381,11 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     if (!Q) return HG_ERR_INVALID_ARG;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
     scale = eff_scale(scale, D);
-    const int64_t rows = (int64_t)B * Hq;
+    const int nq = c->opt_nq;
+    const int64_t rows = (int64_t)B * nq * Hq;
     const LevelDev lv = to_dev(*level, B);
     const Parts parts = carve(c, rows, D);
-    const LevelPlan plan = plan_level(c, lv, Hkv, Hq / Hkv, D, parts.cap);
+    const LevelPlan plan = plan_level(c, lv, Hkv, nq * (Hq / Hkv), D, parts.cap);
     const int ns = plan.ns;
     hipStream_t s = c->stream;
     if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
@@ -384,13 +394,13 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
             rc = fill_empty(O, o_dtype, LSE, rows, D, s);
             if (rc) return rc;
         }
-        return run_level(Q, lv, plan, B, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
+        return run_level(Q, lv, plan, B, nq, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
     }
     if (lv.seq_off) {
         rc = fill_empty(nullptr, HG_F32, parts.l(0), rows * ns, D, s);
         if (rc) return rc;
     }
-    rc = run_level(Q, lv, plan, B, Hq, Hkv, D, scale, parts_out(parts, 0), s);
+    rc = run_level(Q, lv, plan, B, nq, Hq, Hkv, D, scale, parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(ns, parts, 0, D, O, o_dtype, LSE, s);
 }
@@ -407,27 +417,28 @@ int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, con
                    const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
                    float* LSE) {
     if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
-    int rc = check_shape(B, Hq, Hkv, D);
+    int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
     if (B == 0) return HG_OK;
     if (!Q || !offsets || !lengths) return HG_ERR_INVALID_ARG;
     if (max_len > 0 && (!Ks || !Vs)) return HG_ERR_INVALID_ARG;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
     scale = eff_scale(scale, D);
-    const int64_t rows = (int64_t)B * Hq;
+    const int nq = c->opt_nq;
+    const int64_t rows = (int64_t)B * nq * Hq;
     hipStream_t s = c->stream;
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, Hkv);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B * nq, Hkv);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
         p.nchunks = ceil_div(max_len, p.chunk);
     }
     if (p.nchunks == 1)
-        return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
+        return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
                           direct_out(O, o_dtype, LSE), s);
-    rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
+    rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
                     parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
@@ -460,7 +471,7 @@ static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* l
                        void* O_out, int o_dtype) {
     if (!c || !O_out || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
     if (n_levels < 0 || n_levels > HG_MAX_LEVELS || (n_levels > 0 && !levels)) return HG_ERR_INVALID_ARG;
-    int rc = check_shape(B, Hq, Hkv, D);
+    int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
     for (int i = 0; i < n_levels; ++i) {
         rc = check_level(&levels[i], Hkv, D);
@@ -479,7 +490,8 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
     if (B == 0) return HG_OK;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
     scale = eff_scale(scale, D);
-    const int64_t rows = (int64_t)B * Hq;
+    const int nq = c->opt_nq;
+    const int64_t rows = (int64_t)B * nq * Hq;
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
     const Parts parts = carve(c, rows, D);
@@ -495,22 +507,22 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         int T = 1;
         for (int i = 0; i < n_levels; ++i) {
             const long long seqs = levels[i].kv_off ? levels[i].max_seqs : B;
-            flops += 4.0 * levels[i].n_blocks * (double)levels[i].max_rows * seqs * Hq * D;
-            const long long tiles = (seqs * G + kPrefixRowsWide - 1) / kPrefixRowsWide;
-            if (seqs * G > kPrefixRowsNarrow && tiles <= 32 && tiles > T) T = (int)tiles;
+            flops += 4.0 * levels[i].n_blocks * (double)levels[i].max_rows * seqs * nq * Hq * D;
+            const long long tiles = (seqs * nq * G + kPrefixRowsWide - 1) / kPrefixRowsWide;
+            if (seqs * nq * G > kPrefixRowsNarrow && tiles <= 32 && tiles > T) T = (int)tiles;
         }
-        const double bytes = 4.0 * B * (0.75 * max_len) * Hkv * D;   // K and V, bf16; mean length taken as 0.75 max_len
+        const double bytes = 4.0 * B * nq * (0.75 * max_len) * Hkv * D;   // K and V, bf16; mean length taken as 0.75 max_len
         wide_slots = pick_wide_slots(flops, bytes, T);
     }
     for (int i = 0; i < n_levels; ++i) {
         LevelDev d = to_dev(levels[i], B);
         if (d.max_rows == 0 || d.max_seqs == 0) continue;  // empty level contributes nothing
         lv[nlev] = d;
-        plan[nlev] = plan_level(c, d, Hkv, G, D, parts.cap, wide_slots);
+        plan[nlev] = plan_level(c, d, Hkv, nq * G, D, parts.cap, wide_slots);
         ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
-    SuffixPlan sp = plan_suffix(c, max_len, G, B, Hkv);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B * nq, Hkv);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
@@ -522,7 +534,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
             sp.chunk = round_up(ceil_div(max_len, sp.nchunks), 32);
             sp.nchunks = ceil_div(max_len, sp.chunk);
         } else if (big >= 0) {
-            plan[big] = plan_level(c, lv[big], Hkv, G, D, ns[big] - 1, wide_slots);
+            plan[big] = plan_level(c, lv[big], Hkv, nq * G, D, ns[big] - 1, wide_slots);
             ns[big] = plan[big].ns;
         } else {
             return HG_ERR_WORKSPACE;
@@ -567,7 +579,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
     auto enqueue_suffix = [&]() -> int {
         if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
-        const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, sp.chunk,
+        const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, sp.chunk,
                                  sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx);
         if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
@@ -578,7 +590,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         int part = 0;
         for (int i = 0; i < nlev; ++i) {
             if (!mark(1 + i, 0, s)) return HG_ERR_HIP;
-            const int r = run_level(Q, lv[i], plan[i], B, Hq, Hkv, D, scale, parts_out(parts, part), s);
+            const int r = run_level(Q, lv[i], plan[i], B, nq, Hq, Hkv, D, scale, parts_out(parts, part), s);
             if (r) return r;
             if (!mark(1 + i, 1, s)) return HG_ERR_HIP;
             part += ns[i];
@@ -619,7 +631,8 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (B == 0) return HG_OK;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
     scale = eff_scale(scale, D);
-    const int64_t rows = (int64_t)B * Hq;
+    const int nq = c->opt_nq;
+    const int64_t rows = (int64_t)B * nq * Hq;
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
     const Parts parts = carve(c, rows, D);
@@ -640,7 +653,7 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
         chunk = round_up(ceil_div((int)nmax, cap), 32);
         nchunks = ceil_div((int)nmax, chunk);
     }
-    rc = run_decode(Q, n_levels, lv, has_suffix ? Ks : nullptr, Vs, offsets, has_suffix ? lengths : nullptr, max_len, B, Hq,
+    rc = run_decode(Q, n_levels, lv, has_suffix ? Ks : nullptr, Vs, offsets, has_suffix ? lengths : nullptr, max_len, B, nq, Hq,
                     Hkv, D, scale, chunk, nchunks, pick_gt(G), parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(nchunks, parts, 0, D, O_out, o_dtype, LSE_out, s);

@@ -203,7 +203,9 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     const int gb = (int)(u % GB); u /= GB;
     const int kvh = (int)(u % a.Hkv); u /= a.Hkv;
     const int c = (int)(u % a.nchunks);
-    const int b = (int)(u / a.nchunks);
+    const int bq = (int)(u / a.nchunks);     // (sequence, query) pair: b*nq + t
+    const int b = bq / a.nq;
+    const int tq = bq % a.nq;
     const int h0 = kvh * a.G + gb * GT;  // first query head of this work item
 
     DecodeState<D, GT> st;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         const int col = (lane % LPR) * 8;
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            const uint4 qv = *reinterpret_cast<const uint4*>(a.Q + ((int64_t)b * a.Hq + h0 + g) * D + col);
+            const uint4 qv = *reinterpret_cast<const uint4*>(a.Q + ((int64_t)bq * a.Hq + h0 + g) * D + col);
             st.q[g][0] = bf16_lo(qv.x) * qs; st.q[g][1] = bf16_hi(qv.x) * qs;
             st.q[g][2] = bf16_lo(qv.y) * qs; st.q[g][3] = bf16_hi(qv.y) * qs;
             st.q[g][4] = bf16_lo(qv.z) * qs; st.q[g][5] = bf16_hi(qv.z) * qs;
@@ -235,7 +237,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         pos += count;
     }
     if (a.lengths) {
-        int count = min(a.lengths[b], a.max_len);
+        // the nq queries of a sequence are its last nq suffix tokens: query t does not see the later ones
+        int count = min(a.lengths[b], a.max_len) - (a.nq - 1 - tq);
         if (count < 0) count = 0;
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
         if (s0 < s1) decode_span<D, GT, true>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         }
         if (lane < LPR) {
             const float inv = l > 0.f ? 1.0f / l : 0.f;
-            const int64_t idx = (int64_t)b * a.Hq + h0 + g;
+            const int64_t idx = (int64_t)bq * a.Hq + h0 + g;
             const int64_t e = (int64_t)c * a.out.part_stride_O + idx * D + lane * 8;
             if (a.out.bf16) {
                 uint4 v;

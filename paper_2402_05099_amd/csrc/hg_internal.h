@@ -22,7 +22,7 @@ struct LevelDev {
     int max_seqs;
 };
 
-// Where a kernel puts a partial (or final) result for query row idx = b*Hq + h.
+// Where a kernel puts a partial (or final) result for query row idx = (b*nq + t)*Hq + h.
 struct OutDev {
     void* O;          // [rows, D] fp32 or bf16
     float* LSE;       // [rows]
@@ -47,6 +47,7 @@ struct PrefixArgs {
     const uint16_t* Q;
     LevelDev lv;
     int B, Hq, Hkv, G;
+    int nq;           // queries per sequence: a sequence contributes nq*G rows per KV head, row = t*G + g
     int mtiles;       // query-row tiles per (block, KV head)
     int nsplit;       // key-range splits per block
     int chunk;        // keys per split (multiple of the key tile)
@@ -67,9 +68,10 @@ struct DecodeArgs {
     const int32_t* lengths;   // null: no suffix
     int max_len;
     int B, Hq, Hkv, G;
+    int nq;           // queries per sequence; query t sees suffix rows [0, length - (nq-1-t))
     int chunk;        // keys per work item
     int nchunks;      // work items per (sequence, KV head, query-head group)
-    int64_t units;    // B * nchunks * Hkv * (G / GT)
+    int64_t units;    // B * nq * nchunks * Hkv * (G / GT)
     float scale;
     OutDev out;       // part index = chunk
 };

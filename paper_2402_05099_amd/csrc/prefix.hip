@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
         kv0 = a.lv.kv_off[g];
         kv1 = min(a.lv.kv_off[g + 1], kv0 + a.lv.max_rows);
     }
-    const int nrows = (seq1 - seq0) * a.G;
+    const int rps = a.nq * a.G;            // query rows of one sequence for this KV head: (query t, head g) at t*G + g
+    const int nrows = (seq1 - seq0) * rps;
     const int row0 = mt * kPrefixRowsNarrow;
     if (row0 >= nrows) return;
     const int ks = kv0 + sp * a.chunk;
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     const int r = row0 + w * 32 + lq;     // this lane's query row inside the block
     const bool rv = r < nrows;
     const int rr = rv ? r : 0;
-    const int64_t qidx = (int64_t)(seq0 + rr / a.G) * a.Hq + kvh * a.G + rr % a.G;  // b*Hq + h
+    const int64_t qidx = ((int64_t)(seq0 + rr / rps) * a.nq + (rr % rps) / a.G) * a.Hq + kvh * a.G + rr % a.G;  // (b*nq + t)*Hq + h
 
     float* const Of = static_cast<float*>(a.out.O) + sp * a.out.part_stride_O + qidx * D;
     uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + sp * a.out.part_stride_O + qidx * D;

@@ -105,7 +105,8 @@ __device__ __forceinline__ void wide_piece(const PrefixArgs& a, unsigned char* s
     const int r = row0 + w * 32 + lq;     // this lane's query row inside the block
     const bool rv = r < nrows;
     const int rr = rv ? r : 0;
-    const int64_t qidx = (int64_t)(seq0 + rr / a.G) * a.Hq + kvh * a.G + rr % a.G;  // b*Hq + h
+    const int rps = a.nq * a.G;           // query rows of one sequence for this KV head: (query t, head g) at t*G + g
+    const int64_t qidx = ((int64_t)(seq0 + rr / rps) * a.nq + (rr % rps) / a.G) * a.Hq + kvh * a.G + rr % a.G;  // (b*nq + t)*Hq + h
 
     if (ks >= ke) {
         if (rv) {
@@ -344,7 +345,8 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
             kv0 = a.lv.kv_off[g];
             kv1 = min(a.lv.kv_off[g + 1], kv0 + a.lv.max_rows);
         }
-        const int nrows = (seq1 - seq0) * a.G;
+        const int rps = a.nq * a.G;
+        const int nrows = (seq1 - seq0) * rps;
         const int mt = rg * p.T + member;
         const int sp = team - (int)(((long long)c * p.n_c) / p.quota);    // piece index inside the column
         const int ks = kv0 + k0 * KT;
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
             const int tid = threadIdx.x;
             const int r = mt * kPrefixRowsWide + tid;
             if (tid < kPrefixRowsWide && r < nrows) {
-                const int64_t qidx = (int64_t)(seq0 + r / a.G) * a.Hq + kvh * a.G + r % a.G;
+                const int64_t qidx = ((int64_t)(seq0 + r / rps) * a.nq + (r % rps) / a.G) * a.Hq + kvh * a.G + r % a.G;
                 for (int q = sp + 1; q < p.nparts; ++q) a.out.LSE[q * a.out.part_stride_L + qidx] = -INFINITY;
             }
         }
@@ -368,6 +370,7 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
 // Work partition of the persistent kernel for a level (host side).  Returns false when the level does not fit
 // (more than max_parts partial results per row would be needed).
 bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slots_per_xcd, WidePlan* out) {
+    // G here is the number of query rows per sequence and KV head (queries per sequence x heads per group)
     WidePlan p{};
     const long long rows = (long long)lv.max_seqs * G;
     const int mtiles = (int)((rows + kPrefixRowsWide - 1) / kPrefixRowsWide);

@@ -35,8 +35,17 @@ class DeviceWorkload:
     max_len: int
 
     @property
+    def nq(self) -> int:
+        return int(self.Q.shape[1]) if self.Q.dim() == 4 else 1
+
+    @property
     def rows(self) -> int:
-        return self.B * self.Hq
+        return self.B * self.nq * self.Hq
+
+    @property
+    def lead(self):
+        """Leading shape of O and LSE: (B, Hq), or (B, nq, Hq) with several queries per sequence."""
+        return tuple(self.Q.shape[:-1])
 
 
 def to_device(w, device="cuda:0") -> DeviceWorkload:
@@ -58,18 +67,18 @@ def to_device(w, device="cuda:0") -> DeviceWorkload:
 
 
 def make_context(dw: DeviceWorkload, parts: int = 24, device: int = 0) -> hb.Context:
-    return hb.Context(device, hb.hg_workspace_bytes(dw.B, dw.Hq, dw.D, parts))
+    return hb.Context(device, hb.hg_workspace_bytes(dw.B * dw.nq, dw.Hq, dw.D, parts))
 
 
 def hydragen(ctx: hb.Context, dw: DeviceWorkload, out_dtype=torch.bfloat16, want_lse: bool = True):
-    O = torch.empty((dw.B, dw.Hq, dw.D), dtype=out_dtype, device=dw.Q.device)
-    L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device=dw.Q.device) if want_lse else None
+    O = torch.empty(dw.lead + (dw.D,), dtype=out_dtype, device=dw.Q.device)
+    L = torch.empty(dw.lead, dtype=torch.float32, device=dw.Q.device) if want_lse else None
     hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
     return O, L
 
 
 def naive(ctx: hb.Context, dw: DeviceWorkload, out_dtype=torch.bfloat16, want_lse: bool = True):
-    O = torch.empty((dw.B, dw.Hq, dw.D), dtype=out_dtype, device=dw.Q.device)
-    L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device=dw.Q.device) if want_lse else None
+    O = torch.empty(dw.lead + (dw.D,), dtype=out_dtype, device=dw.Q.device)
+    L = torch.empty(dw.lead, dtype=torch.float32, device=dw.Q.device) if want_lse else None
     hb.hg_naive_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
     return O, L

@@ -96,7 +96,7 @@ class Workload:
     Hkv: int
     D: int
     scale: float
-    Q: np.ndarray                      # uint16 [B, Hq, D]
+    Q: np.ndarray                      # uint16 [B, Hq, D], or [B, nq, Hq, D] with nq > 1 queries per sequence
     levels: List[Level]
     Ks: np.ndarray                     # uint16 [T, Hkv, D]
     Vs: np.ndarray                     # uint16 [T, Hkv, D]
@@ -104,6 +104,11 @@ class Workload:
     lengths: np.ndarray                # int32 [B]
     seed: int = 0
     notes: dict = field(default_factory=dict)
+
+    @property
+    def nq(self) -> int:
+        """Queries per sequence (App. B's num_queries): the last nq tokens of every suffix are queried at once."""
+        return int(self.Q.shape[1]) if self.Q.ndim == 4 else 1
 
     @property
     def G(self) -> int:
@@ -149,11 +154,13 @@ def make_workload(
     q_gain: float = 1.0,
     plant: Optional[str] = None,  # None | "suffix" | "prefix"
     lengths: Optional[np.ndarray] = None,
+    nq: int = 1,
 ) -> Workload:
     """Build a workload.  Tensor ids (fixed): Q=0, level l K=10+2l, V=11+2l, lengths=90, Ks=100, Vs=101.
 
     Suffix lengths are integers uniform on [len_lo, len_hi] inclusive.
     `q_gain` scales Q before the bf16 cast (q_gain=4 gives a peaked softmax).
+    `nq` > 1 draws Q as [B, nq, Hq, D]: nq queries per sequence (the last nq suffix tokens).
     `plant` overwrites a few K rows with 2*q so that one key dominates a
     query's softmax: in the suffix (every sequence, its middle row, first
     query head of each KV group) or in each shared block of level 0 (rows
@@ -161,7 +168,8 @@ def make_workload(
     """
     assert Hq % Hkv == 0
     G = Hq // Hkv
-    Q = normal_bf16(seed, 0, (B, Hq, D), gain=q_gain)
+    assert nq >= 1 and (nq == 1 or plant is None), "planted keys are defined for one query per sequence"
+    Q = normal_bf16(seed, 0, (B, Hq, D) if nq == 1 else (B, nq, Hq, D), gain=q_gain)
     levels = []
     for li, (Gn, rows, seqs) in enumerate(level_specs):
         assert Gn * seqs <= B

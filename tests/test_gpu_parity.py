@@ -24,8 +24,8 @@ def outputs(dw, dtype=torch.float32, canary=True):
     pad = 256
     fo = torch.full((n + 2 * pad,), float("nan"), dtype=dtype, device="cuda:0")
     fl = torch.full((dw.rows + 2 * pad,), float("nan"), dtype=torch.float32, device="cuda:0")
-    O = fo[pad:pad + n].view(dw.B, dw.Hq, dw.D)
-    L = fl[pad:pad + dw.rows].view(dw.B, dw.Hq)
+    O = fo[pad:pad + n].view(dw.lead + (dw.D,))
+    L = fl[pad:pad + dw.rows].view(dw.lead)
 
     def intact():
         torch.cuda.synchronize()
@@ -315,4 +315,45 @@ def test_error_paths_launch_nothing():
     torch.cuda.synchronize()
     assert float(O.min()) == 7.0 and float(L.min()) == 7.0  # nothing was written
     assert hb.strerror(hb.HG_ERR_WORKSPACE) == "workspace too small"
+    ctx.close()
+
+
+@pytest.mark.parametrize("nq", [2, 5])
+@pytest.mark.parametrize("shape", ["mha", "gqa_tree", "d64"])
+def test_several_queries_per_sequence(nq, shape):
+    """App. B's num_queries > 1: Q [B, nq, Hq, D]; query t sees the suffix up to its own token (suffixes shorter than nq included)."""
+    say(f"several queries nq={nq} {shape}")
+    def lengths(B, hi, seed):
+        ln = np.random.default_rng(seed).integers(0, hi + 1, size=B).astype(np.int32)
+        ln[:4] = [0, 1, nq - 1, nq]          # suffixes shorter than, and exactly as long as, the query block
+        return ln
+    if shape == "mha":       # 120 (nq=2) or 300 (nq=5) query rows per KV head: 128-row and persistent 256-row kernels
+        w = wl.make_workload("nq_mha", 51, 60, 4, 4, 128, [(1, 700, 60)], 0, 0, lengths=lengths(60, 90, 1), nq=nq)
+    elif shape == "gqa_tree":
+        w = wl.make_workload("nq_tree", 52, 48, 8, 2, 128, [(1, 150, 48), (4, 77, 12)], 0, 0, lengths=lengths(48, 40, 2), nq=nq)
+    else:
+        w = wl.make_workload("nq_d64", 53, 21, 4, 2, 64, [(1, 100, 21)], 0, 0, lengths=lengths(21, 70, 3), nq=nq)
+    assert w.lengths.min() < nq
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=24)
+    Oref, Lref = oracle.attention(w)
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L = dev.hydragen(ctx, dw, dtype)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), Oref, Lref, f"hydragen nq={nq} {shape} {dtype}", out_bf16=dtype == torch.bfloat16)
+    O, L = dev.naive(ctx, dw, torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, f"naive nq={nq} {shape}")
+    # the parts on their own
+    Os, Ls, intact = outputs(dw)
+    hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, Os, Ls, dw.scale)
+    assert intact()
+    Or, Lr = oracle.attention(w, levels=[], suffix=True)
+    check(to_np(Os), to_np(Ls), Or, Lr, f"suffix nq={nq} {shape}")
+    for li in range(len(dw.levels)):
+        Op, Lp, intact = outputs(dw)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[li], Op, Lp, dw.scale)
+        assert intact()
+        Or, Lr = oracle.attention(w, levels=[li], suffix=False)
+        check(to_np(Op), to_np(Lp), Or, Lr, f"level {li} nq={nq} {shape}")
     ctx.close()

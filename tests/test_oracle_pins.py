@@ -359,3 +359,75 @@ def test_planted_key_dominates():
         row = int(w.offsets[b]) + int(w.lengths[b]) // 2
         v = _widen(w.Vs[row])  # [Hkv,D]
         assert np.abs(O[b] - v).max() < 1e-2
+
+
+# ---- several queries per sequence (App. B's num_queries > 1; causal reading of the design doc) ------------------------
+
+def _nq_workload():
+    lengths = np.array([0, 1, 2, 3, 4, 9, 5], dtype=np.int32)   # some shorter than nq, one empty
+    return wl.make_workload("nq", 91, 7, 4, 2, 16, [(1, 6, 7), (2, 3, 3)], 0, 0, lengths=lengths, nq=3)
+
+
+def test_several_queries_brute_force_with_explicit_visibility():
+    """Pure-Python exact sums; query t of sequence b sees every shared row and suffix rows 0 .. L_b - nq + t."""
+    w = _nq_workload()
+    assert w.nq == 3 and w.Q.shape == (7, 3, 4, 16)
+    O, L = oracle.attention(w)
+    assert O.shape == (7, 3, 4, 16) and L.shape == (7, 3, 4)
+    G = w.Hq // w.Hkv
+    for b in range(w.B):
+        for t in range(w.nq):
+            for h in range(w.Hq):
+                kvh = h // G
+                q = _widen(w.Q[b, t, h]).tolist()
+                rows = []
+                for li, r0, r1 in w.kv_rows_of(b):
+                    rows += [(_widen(w.levels[li].K[r, kvh]).tolist(), _widen(w.levels[li].V[r, kvh]).tolist()) for r in range(r0, r1)]
+                last_visible = int(w.lengths[b]) - w.nq + t      # index of the query's own suffix row
+                for i in range(int(w.lengths[b])):
+                    if i <= last_visible:
+                        r = int(w.offsets[b]) + i
+                        rows.append((_widen(w.Ks[r, kvh]).tolist(), _widen(w.Vs[r, kvh]).tolist()))
+                if not rows:
+                    assert np.all(O[b, t, h] == 0) and L[b, t, h] == -np.inf
+                    continue
+                e = [math.exp(math.fsum(qi * ki for qi, ki in zip(q, k)) * w.scale) for k, _ in rows]
+                den = math.fsum(e)
+                Ob = [math.fsum(ei * v[d] for ei, (_, v) in zip(e, rows)) / den for d in range(w.D)]
+                assert np.allclose(O[b, t, h], Ob, rtol=0, atol=1e-12)
+                assert abs(L[b, t, h] - math.log(den)) < 1e-12
+
+
+def test_several_queries_equal_single_query_calls_on_shortened_suffixes():
+    """Query t of an nq-query call is the one-query problem whose suffix ends at that token."""
+    w = _nq_workload()
+    O, L = oracle.attention(w)
+    lv = [(l.K, l.V, l.kv_off, l.seq_off) for l in w.levels]
+    for t in range(w.nq):
+        shortened = np.maximum(w.lengths - (w.nq - 1 - t), 0).astype(np.int32)
+        O1, L1 = oracle.attention_arrays(np.ascontiguousarray(w.Q[:, t]), w.Hkv, lv, w.Ks, w.Vs, w.offsets, shortened, w.scale)
+        assert np.array_equal(O[:, t], O1) and np.array_equal(L[:, t], L1)
+    # the last query is the plain decode query of the paper (num_queries = 1)
+    O1, L1 = oracle.attention_arrays(np.ascontiguousarray(w.Q[:, -1]), w.Hkv, lv, w.Ks, w.Vs, w.offsets, w.lengths, w.scale)
+    assert np.array_equal(O[:, -1], O1)
+
+
+def test_several_queries_library_softmax_with_causal_mask():
+    """scipy softmax over all rows with the masked scores set to -inf."""
+    w = _nq_workload()
+    O, L = oracle.attention(w)
+    G = w.Hq // w.Hkv
+    for b in (2, 4, 5):
+        Kc = [_widen(w.levels[li].K[r0:r1]) for li, r0, r1 in w.kv_rows_of(b)]
+        Vc = [_widen(w.levels[li].V[r0:r1]) for li, r0, r1 in w.kv_rows_of(b)]
+        nshared = sum(k.shape[0] for k in Kc)
+        o, n = int(w.offsets[b]), int(w.lengths[b])
+        K = np.repeat(np.concatenate(Kc + [_widen(w.Ks[o:o + n])]), G, axis=1)
+        V = np.repeat(np.concatenate(Vc + [_widen(w.Vs[o:o + n])]), G, axis=1)
+        for t in range(w.nq):
+            S = np.einsum("hd,nhd->hn", _widen(w.Q[b, t]), K) * w.scale
+            pos = np.arange(n)
+            S[:, nshared:][:, pos > n - w.nq + t] = -np.inf
+            Pm = scipy.special.softmax(S, axis=1)
+            assert np.allclose(O[b, t], np.einsum("hn,nhd->hd", Pm, V), rtol=0, atol=1e-12)
+            assert np.allclose(L[b, t], scipy.special.logsumexp(S, axis=1), rtol=0, atol=1e-12)
