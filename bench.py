@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--prefix-kernel", type=int, default=0, help="0 auto, 1 128-row workgroups, 2 256-row workgroups")
+    ap.add_argument("--paged", type=int, default=0, help="rows per page: the suffix cache is a page pool read through a page table (0 = packed rows, the default)")
+    ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
     ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
     args = ap.parse_args()
 
@@ -90,8 +92,16 @@ def main() -> int:
     O = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.bfloat16, device="cuda:0")
     L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
 
+    kv = None
+    if args.paged:
+        kv = dev.paged_to_device(wl.make_paged(w, args.paged, reserve=args.append_steps))
+        torch.cuda.synchronize()
+
     def step():
-        hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+        if kv is not None:
+            hb.hg_hydragen_attn_paged(ctx, dw.Q, dw.levels, kv, dw.lengths, dw.max_len, O, L, dw.scale)
+        else:
+            hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
 
     for _ in range(args.warmup):
         step()
@@ -186,6 +196,30 @@ def main() -> int:
         torch.cuda.synchronize()
         naive_ms = e0.elapsed_time(e1) / args.naive_steps
 
+    # ---- KV-cache update of a decode step (optional): the new token's K/V rows appended on the device --------------
+    append_ms = None
+    if args.append_steps > 0:
+        Kn, Vn = wl.new_rows(w)
+        dKn, dVn = dev.bf16_tensor(Kn, "cuda:0"), dev.bf16_tensor(Vn, "cuda:0")
+        dlen = dw.lengths.clone()
+        cap = w.max_len + args.append_steps
+        if kv is None:
+            hK, hV, hoff, cap = wl.with_room(w, args.append_steps)
+            dK, dV, doff = dev.bf16_tensor(hK, "cuda:0"), dev.bf16_tensor(hV, "cuda:0"), torch.from_numpy(hoff).cuda()
+            del hK, hV
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.append_steps):
+            if kv is not None:
+                hb.hg_kv_append_paged(ctx, dKn, dVn, kv, dlen, cap)
+            else:
+                hb.hg_kv_append(ctx, dKn, dVn, dK, dV, doff, dlen, cap)
+        e1.record()
+        torch.cuda.synchronize()
+        append_ms = e0.elapsed_time(e1) / args.append_steps
+        assert bool((dlen == dw.lengths + args.append_steps).all())
+
     # ---- CPU oracle on a bounded sample: baseline figure + parity spot check of the timed configuration --------
     cpu = None
     parity = None
@@ -223,7 +257,7 @@ def main() -> int:
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
                    "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
                    "suffix_len": [int(w.lengths.min()), int(w.lengths.max())], "suffix_tokens": int(w.T), "seed": w.seed,
-                   "overlap_streams": args.overlap},
+                   "overlap_streams": args.overlap, "suffix_cache": f"paged, {args.paged} rows per page" if args.paged else "packed rows"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
@@ -233,6 +267,7 @@ def main() -> int:
                                   "merge": float(st_timed[1 + nlev]), "note": "kernels overlap: each span includes the other's work"},
         "naive": None if naive_ms is None else {"ms_per_step": naive_ms, "queries_per_s": B / (naive_ms * 1e-3),
                                                  "speedup_hydragen_over_naive": naive_ms / ms_per_step},
+        "kv_append_ms": append_ms,
         "parity": parity,
     }
     print(json.dumps(out))

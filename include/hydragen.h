@@ -159,6 +159,55 @@ int hg_hydragen_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* l
                      void* O_out, int o_dtype, float* LSE_out);
 
 /*
+ * Paged suffix cache.  Sec. 3.5 contrasts Hydragen's plain suffix cache with PagedAttention's paged one (see also
+ * Sec. 1 and Sec. 6); the decomposition itself (Sec. 3.1) does not care how suffix rows are stored, so the suffix part may also
+ * read through a page table.  K, V: bf16 [n_pages * page_size, Hkv, D], one pool of fixed-size pages shared by all
+ * sequences.  Suffix row j of sequence b is pool row page_table[b * table_stride + j / page_size] * page_size +
+ * j % page_size.  page_table is DEVICE int32 [B, table_stride] and is read on the device at run time; only entries
+ * of pages that hold rows below lengths[b] are read, and an entry outside [0, n_pages) is clamped into that range
+ * (so a bad table gives wrong numbers, never an access outside the pool).  page_size is a power of two in
+ * [16, 1024]; table_stride >= ceil(max_len / page_size); n_pages * page_size * Hkv * D < 2^31.
+ * Which page a sequence gets is the caller's business (a host-side allocator): the library only reads the table.
+ */
+typedef struct {
+    void* K;
+    void* V;
+    const int32_t* page_table;
+    int page_size;
+    int table_stride;
+    int n_pages;
+} hg_paged_kv;
+
+/*
+ * hg_suffix_attn / hg_hydragen_attn with the suffix rows read through a page table: same results as the
+ * calls above on the rows that the table designates (lengths: DEVICE int32[B], rows above max_len are ignored).
+ * A work item of the suffix kernel covers at most 32 pages, so the workspace must have room for
+ * ceil(max_len / (32 * page_size)) partial results (plus one per shared level), else HG_ERR_WORKSPACE.
+ */
+int hg_suffix_attn_paged(hg_ctx* ctx, const void* Q, const hg_paged_kv* kv, const int32_t* lengths, int max_len,
+                         int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype, float* LSE);
+int hg_hydragen_attn_paged(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* levels,
+                           const hg_paged_kv* kv, const int32_t* lengths, int max_len,
+                           int B, int Hq, int Hkv, int D, float scale,
+                           void* O_out, int o_dtype, float* LSE_out);
+
+/*
+ * The KV-cache update of a decode step (Sec. 2.2: the keys and values of every earlier token are kept, and each
+ * step adds those of the newest token; Sec. 3.5: suffix lengths change from step to step under a captured graph, so
+ * the update runs on the device).  Knew, Vnew: bf16 [B, nq, Hkv, D], the rows of the nq new tokens of every
+ * sequence (nq = HG_OPT_NUM_QUERIES, 1 by default).  Row t of sequence b is written to suffix row
+ * lengths[b] + t (addressed as in hg_suffix_attn, or through the page table, whose entry for that page must already
+ * be set), and lengths[b] becomes min(lengths[b] + nq, capacity): rows at or above `capacity` (a host value, the
+ * rows reserved per sequence) are dropped.  lengths is DEVICE int32[B], read and written on the device; nothing
+ * comes back to the host.  Calling hg_kv_append and then an attention call with max_len >= the new lengths is
+ * one decode step: the newest token's query then sees its own key as the last suffix row.
+ */
+int hg_kv_append(hg_ctx* ctx, const void* Knew, const void* Vnew, void* Ks, void* Vs,
+                 const int32_t* offsets, int32_t* lengths, int capacity, int B, int Hkv, int D);
+int hg_kv_append_paged(hg_ctx* ctx, const void* Knew, const void* Vnew, const hg_paged_kv* kv,
+                       int32_t* lengths, int capacity, int B, int Hkv, int D);
+
+/*
  * Non-decomposed comparison (the behaviour Sec. 1 and Sec. 2.3 attribute to per-sequence decode kernels):
  * same arguments and result as hg_hydragen_attn, but every sequence walks its whole key list
  * (shared blocks, then suffix) by itself, so shared rows are re-read once per sequence.

@@ -13,6 +13,8 @@ from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
+from .kvcache import kv_append, kv_append_paged, paged_to_packed  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hydragen_oracle.c")
 _LIB = os.path.join(_HERE, "libhydragen_oracle.so")

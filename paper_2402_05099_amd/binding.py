@@ -28,7 +28,7 @@ LIB_PATH = os.environ.get("HYDRAGEN_LIB") or os.path.join(os.path.dirname(os.pat
 EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
-    "hg_strerror",
+    "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
 )
 
 
@@ -43,6 +43,13 @@ class hg_level(ctypes.Structure):
         ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("n_blocks", ctypes.c_int),
         ("kv_off", ctypes.c_void_p), ("seq_off", ctypes.c_void_p),
         ("max_rows", ctypes.c_int), ("max_seqs", ctypes.c_int),
+    ]
+
+
+class hg_paged_kv(ctypes.Structure):
+    _fields_ = [
+        ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int), ("table_stride", ctypes.c_int), ("n_pages", ctypes.c_int),
     ]
 
 
@@ -80,6 +87,15 @@ def lib() -> ctypes.CDLL:
         L.hg_hydragen_attn.restype = ci
         L.hg_naive_attn.argtypes = fused
         L.hg_naive_attn.restype = ci
+        L.hg_suffix_attn_paged.argtypes = [vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_suffix_attn_paged.restype = ci
+        L.hg_hydragen_attn_paged.argtypes = [vp, vp, ci, ctypes.POINTER(hg_level), ctypes.POINTER(hg_paged_kv), vp, ci,
+                                             ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_hydragen_attn_paged.restype = ci
+        L.hg_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci]
+        L.hg_kv_append.restype = ci
+        L.hg_kv_append_paged.argtypes = [vp, vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci]
+        L.hg_kv_append_paged.restype = ci
         L.hg_read_stage_timings.argtypes = [vp, ctypes.POINTER(cf), ci]
         L.hg_read_stage_timings.restype = ci
         L.hg_strerror.argtypes = [ci]
@@ -136,6 +152,23 @@ class Level:
                         None if self.kv_off is None else self.kv_off.data_ptr(),
                         None if self.seq_off is None else self.seq_off.data_ptr(),
                         self.max_rows, self.max_seqs)
+
+
+@dataclass
+class PagedKV:
+    """A paged suffix cache on the device (see hg_paged_kv in include/hydragen.h)."""
+    K: torch.Tensor            # bf16 [n_pages * page_size, Hkv, D]
+    V: torch.Tensor
+    page_table: torch.Tensor   # int32 [B, table_stride] on device
+    page_size: int
+
+    @property
+    def n_pages(self) -> int:
+        return int(self.K.shape[0]) // self.page_size
+
+    def c_struct(self) -> hg_paged_kv:
+        return hg_paged_kv(self.K.data_ptr(), self.V.data_ptr(), self.page_table.data_ptr(), self.page_size,
+                           int(self.page_table.shape[1]), self.n_pages)
 
 
 class Context:
@@ -275,3 +308,65 @@ def hg_hydragen_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, leng
 def hg_naive_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,
                   scale: float = 0.0) -> None:
     _fused(lib().hg_naive_attn, "hg_naive_attn", ctx, Q, levels, Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale)
+
+
+def _want_paged(kv: PagedKV, B: int, D: int) -> int:
+    _want(kv.K, torch.bfloat16, name="paged K"); _want(kv.V, torch.bfloat16, kv.K.shape, "paged V")
+    _want(kv.page_table, torch.int32, name="page_table")
+    if kv.page_table.ndim != 2 or kv.page_table.shape[0] != B or kv.K.shape[2] != D or kv.K.shape[0] % kv.page_size:
+        raise ValueError("paged cache: page_table must be [B, stride] and K [n_pages * page_size, Hkv, D]")
+    return int(kv.K.shape[1])
+
+
+def hg_suffix_attn_paged(ctx: Context, Q, kv: PagedKV, lengths, max_len: int, O, LSE, scale: float = 0.0) -> None:
+    B, Hq, D, lead = _qshape(ctx, Q)
+    Hkv = _want_paged(kv, B, D)
+    _want(Q, torch.bfloat16, name="Q"); _want(lengths, torch.int32, (B,), "lengths")
+    _want(O, O.dtype, lead + (D,), "O"); _want(LSE, torch.float32, lead, "LSE")
+    st = kv.c_struct()
+    _check(lib().hg_suffix_attn_paged(ctx.h, _p(Q), ctypes.byref(st), _p(lengths), max_len, B, Hq, Hkv, D, scale,
+                                      _p(O), _dtype_code(O), _p(LSE)), "hg_suffix_attn_paged")
+
+
+def hg_hydragen_attn_paged(ctx: Context, Q, levels: List[Level], kv: PagedKV, lengths, max_len: int, O_out, LSE_out=None,
+                           scale: float = 0.0) -> None:
+    B, Hq, D, lead = _qshape(ctx, Q)
+    Hkv = _want_paged(kv, B, D)
+    _want(Q, torch.bfloat16, name="Q"); _want(lengths, torch.int32, (B,), "lengths")
+    for lv in levels:
+        _want(lv.K, torch.bfloat16, name="level K"); _want(lv.V, torch.bfloat16, lv.K.shape, "level V")
+    _want(O_out, O_out.dtype, lead + (D,), "O_out")
+    if LSE_out is not None:
+        _want(LSE_out, torch.float32, lead, "LSE_out")
+    n = len(levels)
+    arr = (hg_level * max(n, 1))(*[lv.c_struct() for lv in levels])
+    st = kv.c_struct()
+    _check(lib().hg_hydragen_attn_paged(ctx.h, _p(Q), n, arr, ctypes.byref(st), _p(lengths), max_len, B, Hq, Hkv, D, scale,
+                                        _p(O_out), _dtype_code(O_out), _p(LSE_out)), "hg_hydragen_attn_paged")
+
+
+def _new_rows(ctx: Context, Knew, Vnew):
+    """(B, Hkv, D) of the new rows [B, Hkv, D] or [B, nq, Hkv, D]; tells the context how many rows a sequence adds."""
+    _want(Knew, torch.bfloat16, name="Knew"); _want(Vnew, torch.bfloat16, Knew.shape, "Vnew")
+    B, Hkv, D, _ = _qshape(ctx, Knew)
+    return B, Hkv, D
+
+
+def hg_kv_append(ctx: Context, Knew, Vnew, Ks, Vs, offsets, lengths, capacity: int) -> None:
+    B, Hkv, D = _new_rows(ctx, Knew, Vnew)
+    _want(Ks, torch.bfloat16, name="Ks"); _want(Vs, torch.bfloat16, Ks.shape, "Vs")
+    if tuple(Ks.shape[1:]) != (Hkv, D):
+        raise ValueError("Ks must be [T, Hkv, D]")
+    _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _check(lib().hg_kv_append(ctx.h, _p(Knew), _p(Vnew), _p(Ks), _p(Vs), _p(offsets), _p(lengths), capacity, B, Hkv, D),
+           "hg_kv_append")
+
+
+def hg_kv_append_paged(ctx: Context, Knew, Vnew, kv: PagedKV, lengths, capacity: int) -> None:
+    B, Hkv, D = _new_rows(ctx, Knew, Vnew)
+    if _want_paged(kv, B, D) != Hkv:
+        raise ValueError("paged K must be [n_pages * page_size, Hkv, D]")
+    _want(lengths, torch.int32, (B,), "lengths")
+    st = kv.c_struct()
+    _check(lib().hg_kv_append_paged(ctx.h, _p(Knew), _p(Vnew), ctypes.byref(st), _p(lengths), capacity, B, Hkv, D),
+           "hg_kv_append_paged")

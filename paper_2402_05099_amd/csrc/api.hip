@@ -165,11 +165,13 @@ struct SuffixPlan { int chunk, nchunks, gt; };
 // Work items of the suffix kernel are (sequence, KV head, group of query heads, key chunk), one wavefront each.
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv) {
+// max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv, int max_chunk = 1 << 30) {
     SuffixPlan p;
     p.gt = pick_gt(G);
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
+        if (p.chunk > max_chunk) p.chunk = max_chunk;
     } else {
         p.chunk = 256;
         const long long per_chunk = (long long)B * Hkv * (G / p.gt);
@@ -181,8 +183,9 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv) {
 
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
                const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
-               int gt, const OutDev& out, hipStream_t s) {
+               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}) {
     DecodeArgs a{};
+    a.pg = pg;
     a.Q = static_cast<const uint16_t*>(Q);
     a.n_levels = n_levels;
     for (int i = 0; i < n_levels; ++i) a.lv[i] = lv[i];
@@ -413,14 +416,15 @@ int hg_prefix_attn(hg_ctx* c, const void* Q, const void* Kp, const void* Vp, int
     return hg_prefix_attn_grouped(c, Q, &lv, B, Hq, Hkv, D, scale, O, o_dtype, LSE);
 }
 
-int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, const int32_t* offsets,
-                   const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
-                   float* LSE) {
+// hg_suffix_attn and hg_suffix_attn_paged (pg.table set, offsets unused)
+static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, const int32_t* offsets,
+                       const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
+                       float* LSE, const hg::PagedDev& pg, bool paged) {
     if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
     int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
     if (B == 0) return HG_OK;
-    if (!Q || !offsets || !lengths) return HG_ERR_INVALID_ARG;
+    if (!Q || (!offsets && !paged) || !lengths) return HG_ERR_INVALID_ARG;
     if (max_len > 0 && (!Ks || !Vs)) return HG_ERR_INVALID_ARG;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
     scale = eff_scale(scale, D);
@@ -429,19 +433,55 @@ int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, con
     hipStream_t s = c->stream;
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B * nq, Hkv);
+    const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B * nq, Hkv, max_chunk);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
         p.nchunks = ceil_div(max_len, p.chunk);
     }
+    if (p.chunk > max_chunk) return HG_ERR_WORKSPACE;
     if (p.nchunks == 1)
         return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
-                          direct_out(O, o_dtype, LSE), s);
+                          direct_out(O, o_dtype, LSE), s, pg);
     rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
-                    parts_out(parts, 0), s);
+                    parts_out(parts, 0), s, pg);
     if (rc) return rc;
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
+}
+
+// checks an hg_paged_kv against the rows it must be able to address and translates it
+static int paged_dev(const hg_paged_kv* kv, int rows_per_seq, int Hkv, int D, hg::PagedDev* out) {
+    if (!kv || !out) return HG_ERR_INVALID_ARG;
+    int shift = 0;
+    while ((1 << shift) < kv->page_size && shift < 11) ++shift;
+    if (kv->page_size < 16 || kv->page_size > 1024 || (1 << shift) != kv->page_size) return HG_ERR_INVALID_ARG;
+    if (kv->n_pages < 0 || kv->table_stride < 0) return HG_ERR_INVALID_ARG;
+    if ((int64_t)kv->n_pages * kv->page_size * Hkv * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    if (rows_per_seq > 0) {
+        if (!kv->K || !kv->V || !kv->page_table || kv->n_pages < 1) return HG_ERR_INVALID_ARG;
+        if ((int64_t)kv->table_stride * kv->page_size < rows_per_seq) return HG_ERR_INVALID_ARG;
+    }
+    out->table = kv->page_table;
+    out->shift = shift;
+    out->stride = kv->table_stride;
+    out->n_pages = kv->n_pages;
+    return HG_OK;
+}
+
+int hg_suffix_attn(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, const int32_t* offsets,
+                   const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
+                   float* LSE) {
+    return suffix_impl(c, Q, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, O, o_dtype, LSE, hg::PagedDev{}, false);
+}
+
+int hg_suffix_attn_paged(hg_ctx* c, const void* Q, const hg_paged_kv* kv, const int32_t* lengths, int max_len, int B,
+                         int Hq, int Hkv, int D, float scale, void* O, int o_dtype, float* LSE) {
+    if (max_len < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
+    hg::PagedDev pg{};
+    const int rc = paged_dev(kv, max_len, Hkv, D, &pg);
+    if (rc) return rc;
+    return suffix_impl(c, Q, kv->K, kv->V, nullptr, lengths, max_len, B, Hq, Hkv, D, scale, O, o_dtype, LSE, pg, true);
 }
 
 int hg_merge(hg_ctx* c, int n, const void* const* O_parts, const float* const* LSE_parts, int o_dtype_in, int64_t rows,
@@ -468,7 +508,7 @@ int hg_merge(hg_ctx* c, int n, const void* const* O_parts, const float* const* L
 
 static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
                        const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
-                       void* O_out, int o_dtype) {
+                       void* O_out, int o_dtype, bool paged = false) {
     if (!c || !O_out || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
     if (n_levels < 0 || n_levels > HG_MAX_LEVELS || (n_levels > 0 && !levels)) return HG_ERR_INVALID_ARG;
     int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
@@ -478,14 +518,16 @@ static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* l
         if (rc) return rc;
     }
     if (B > 0 && !Q) return HG_ERR_INVALID_ARG;
-    if (Ks && max_len > 0 && (!Vs || !offsets || !lengths)) return HG_ERR_INVALID_ARG;
+    if (Ks && max_len > 0 && (!Vs || (!offsets && !paged) || !lengths)) return HG_ERR_INVALID_ARG;
     return HG_OK;
 }
 
-int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
-                     const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
-                     float scale, void* O_out, int o_dtype, float* LSE_out) {
-    int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype);
+// hg_hydragen_attn and hg_hydragen_attn_paged (pg.table set, offsets unused)
+static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                      const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
+                      float scale, void* O_out, int o_dtype, float* LSE_out, const hg::PagedDev& pg) {
+    int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype,
+                         pg.table != nullptr);
     if (rc) return rc;
     if (B == 0) return HG_OK;
     if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
@@ -522,7 +564,8 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         ns[nlev] = plan[nlev].ns;
         ++nlev;
     }
-    SuffixPlan sp = plan_suffix(c, max_len, G, B * nq, Hkv);
+    const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
+    SuffixPlan sp = plan_suffix(c, max_len, G, B * nq, Hkv, max_chunk);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
@@ -540,6 +583,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
             return HG_ERR_WORKSPACE;
         }
     }
+    if (has_suffix && sp.chunk > max_chunk) return HG_ERR_WORKSPACE;
     const int np = total_parts();
     hipStream_t s = c->stream;
     if (np == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
@@ -580,7 +624,7 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
         if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
         const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, sp.chunk,
-                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx);
+                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg);
         if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
@@ -621,6 +665,66 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
     if (!mark(nlev + 1, 1, s)) return HG_ERR_HIP;
     if (slot >= 0) c->tcalls += 1;
     return HG_OK;
+}
+
+int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                     const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
+                     float scale, void* O_out, int o_dtype, float* LSE_out) {
+    return fused_impl(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, O_out, o_dtype,
+                      LSE_out, hg::PagedDev{});
+}
+
+int hg_hydragen_attn_paged(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const hg_paged_kv* kv,
+                           const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O_out,
+                           int o_dtype, float* LSE_out) {
+    if (max_len < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
+    hg::PagedDev pg{};
+    const int rc = paged_dev(kv, max_len, Hkv, D, &pg);
+    if (rc) return rc;
+    if (max_len == 0) pg.table = nullptr;   // no suffix rows: the call reduces to the shared levels
+    return fused_impl(c, Q, n_levels, levels, max_len > 0 ? kv->K : nullptr, kv->V, nullptr, lengths, max_len, B, Hq, Hkv, D,
+                      scale, O_out, o_dtype, LSE_out, pg);
+}
+
+// hg_kv_append and hg_kv_append_paged
+static int append_impl(hg_ctx* c, const void* Knew, const void* Vnew, void* Ks, void* Vs, const int32_t* offsets,
+                       int32_t* lengths, int capacity, int B, int Hkv, int D, const hg::PagedDev& pg) {
+    if (!c || B < 0 || Hkv <= 0 || capacity < 0) return HG_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return HG_ERR_UNSUPPORTED;
+    if ((int64_t)B * c->opt_nq * Hkv * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    if (B == 0) return HG_OK;
+    if (!Knew || !Vnew || !lengths || (!offsets && !pg.table)) return HG_ERR_INVALID_ARG;
+    if (capacity > 0 && (!Ks || !Vs)) return HG_ERR_INVALID_ARG;
+    if (capacity == 0) return HG_OK;   // no room anywhere: every new row is dropped, lengths stay
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    hg::AppendArgs a{};
+    a.Knew = static_cast<const uint16_t*>(Knew);
+    a.Vnew = static_cast<const uint16_t*>(Vnew);
+    a.Ks = static_cast<uint16_t*>(Ks);
+    a.Vs = static_cast<uint16_t*>(Vs);
+    a.offsets = offsets;
+    a.lengths = lengths;
+    a.pg = pg;
+    a.capacity = capacity;
+    a.B = B;
+    a.nq = c->opt_nq;
+    a.row_elems = Hkv * D;
+    return hip_rc(hg::launch_kv_append(a, c->stream));
+}
+
+int hg_kv_append(hg_ctx* c, const void* Knew, const void* Vnew, void* Ks, void* Vs, const int32_t* offsets,
+                 int32_t* lengths, int capacity, int B, int Hkv, int D) {
+    return append_impl(c, Knew, Vnew, Ks, Vs, offsets, lengths, capacity, B, Hkv, D, hg::PagedDev{});
+}
+
+int hg_kv_append_paged(hg_ctx* c, const void* Knew, const void* Vnew, const hg_paged_kv* kv, int32_t* lengths,
+                       int capacity, int B, int Hkv, int D) {
+    if (capacity < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
+    hg::PagedDev pg{};
+    const int rc = paged_dev(kv, capacity, Hkv, D, &pg);
+    if (rc) return rc;
+    if (capacity == 0) return HG_OK;
+    return append_impl(c, Knew, Vnew, kv->K, kv->V, nullptr, lengths, capacity, B, Hkv, D, pg);
 }
 
 int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,

@@ -168,6 +168,61 @@ __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16
     }
 }
 
+// The same pass over rows [start, start+n) of sequence b's suffix when the rows live in a paged pool (`start` is a
+// multiple of 32, the span touches at most 64 pages: the host bounds the chunk by 32 pages).  Lane i of the
+// wavefront holds the physical page of the span's i-th logical page; the 4 or 8 keys of one wave-wide load never
+// straddle a page (pages hold at least 16 rows), so the page of a load is wavefront-uniform: one v_readlane and
+// a few scalar instructions per load, the same unpredicated vector loads and the same pipeline as above.
+template <int D, int GT>
+__device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
+                                                  const uint16_t* __restrict__ V, const PagedDev& pg, int b, int start,
+                                                  int n, int Hkv, int kvh, int lane) {
+    constexpr int LPR = D / 8;
+    constexpr int KPW = 64 / LPR;
+    constexpr int U = GT >= 8 ? 2 : 4;
+    constexpr int STEP = KPW * U;
+    const int sub = lane / LPR;
+    const unsigned rstride_b = (unsigned)Hkv * D * 2u;
+    const unsigned colb = (unsigned)(lane % LPR) * 16u;
+    const unsigned subrow = (unsigned)sub * rstride_b + colb;
+    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K + (int64_t)kvh * D));
+    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V + (int64_t)kvh * D));
+    const int shift = pg.shift;
+    const int lp0 = start >> shift;
+    const int lpn = ((start + n - 1) >> shift) - lp0 + 1;
+    int pages = 0;
+    if (lane < lpn) pages = pg.table[(int64_t)b * pg.stride + lp0 + lane];
+    pages = min(max(pages, 0), pg.n_pages - 1);
+    // byte offset of the pool row that holds the span's key i0 (i0: wavefront-uniform multiple of KPW)
+    auto row_base = [&](int i0) -> unsigned {
+        const int pos = start + i0;
+        const int page = __builtin_amdgcn_readlane(pages, ((pos >> shift) - lp0) & 63);
+        return ((unsigned)(page << shift) + (unsigned)(pos & ((1 << shift) - 1))) * rstride_b;
+    };
+    const unsigned safe = row_base(0) + colb;   // lanes past the span read its first row (their scores are masked)
+    auto load = [&](KVBatch<D, U>& bt, int i0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int iu = i0 + u * KPW;
+            const unsigned off = iu + sub < n ? row_base(iu) + subrow : safe;
+            bt.k[u] = ldg128<true>(kb, off);
+            bt.v[u] = ldg128<true>(vb, off);
+        }
+    };
+
+    KVBatch<D, U> ba, bb;
+    load(ba, 0);
+    for (int it = 0; it < n; it += 2 * STEP) {
+        load(bb, it + STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        consume_batch<D, GT, U>(st, ba, it + sub, n);
+        __builtin_amdgcn_sched_barrier(0);
+        load(ba, it + 2 * STEP);
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + STEP < n) consume_batch<D, GT, U>(st, bb, it + STEP + sub, n);
+    }
+}
+
 // rows [begin, begin+count) of the block of level `lv` that covers sequence b (count = 0 if none)
 __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& begin, int& count) {
     if (lv.n_blocks == 1 && lv.seq_off == nullptr) {
@@ -192,7 +247,8 @@ __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& 
 
 // SHARED = false: suffix rows only (the Hydragen suffix part).  SHARED = true: the shared blocks of every level
 // are walked too (the non-decomposed comparison); a separate instantiation so that profiles tell them apart.
-template <int D, int GT, bool SHARED>
+// PAGED (only without SHARED): the suffix rows are read through a page table.
+template <int D, int GT, bool SHARED, bool PAGED>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     constexpr int LPR = D / 8;
     const int lane = threadIdx.x & 63;
@@ -241,7 +297,10 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         int count = min(a.lengths[b], a.max_len) - (a.nq - 1 - tq);
         if (count < 0) count = 0;
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
-        if (s0 < s1) decode_span<D, GT, true>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+        if (s0 < s1) {
+            if constexpr (PAGED) decode_span_paged<D, GT>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
+            else decode_span<D, GT, true>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+        }
     }
 
     // combine the 64/LPR key sub-streams of the wavefront and write (O, LSE)
@@ -287,8 +346,14 @@ static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     if (a.units == 0) return hipSuccess;
     const int64_t grid = (a.units + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.n_levels > 0) decode_kernel<D, GT, true><<<(unsigned)grid, 256, 0, s>>>(a);
-    else decode_kernel<D, GT, false><<<(unsigned)grid, 256, 0, s>>>(a);
+    if (a.pg.table) {
+        if (a.n_levels > 0) return hipErrorInvalidValue;   // the comparison kernel has no paged form
+        decode_kernel<D, GT, false, true><<<(unsigned)grid, 256, 0, s>>>(a);
+    } else if (a.n_levels > 0) {
+        decode_kernel<D, GT, true, false><<<(unsigned)grid, 256, 0, s>>>(a);
+    } else {
+        decode_kernel<D, GT, false, false><<<(unsigned)grid, 256, 0, s>>>(a);
+    }
     return hipGetLastError();
 }
 

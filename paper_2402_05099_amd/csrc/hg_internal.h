@@ -58,6 +58,15 @@ struct PrefixArgs {
     WidePlan wide;    // persistent kernel only
 };
 
+// Page table of a paged suffix cache: suffix row j of sequence b is pool row
+// (table[b*stride + (j >> shift)] << shift) + (j & ((1 << shift) - 1)); page ids are clamped to [0, n_pages).
+struct PagedDev {
+    const int32_t* table;   // null: the suffix is addressed by offsets[b] + j
+    int shift;              // log2(rows per page), 4..10
+    int stride;             // table entries per sequence
+    int n_pages;
+};
+
 struct DecodeArgs {
     const uint16_t* Q;
     int n_levels;
@@ -66,6 +75,7 @@ struct DecodeArgs {
     const uint16_t* Vs;
     const int32_t* offsets;
     const int32_t* lengths;   // null: no suffix
+    PagedDev pg;              // suffix read through a page table when pg.table != null (then offsets is unused)
     int max_len;
     int B, Hq, Hkv, G;
     int nq;           // queries per sequence; query t sees suffix rows [0, length - (nq-1-t))
@@ -85,6 +95,20 @@ struct MergeArgs {
     float* L_out;     // may be null
 };
 
+// KV-cache update of a decode step: nq new rows per sequence appended to the suffix cache, lengths advanced.
+struct AppendArgs {
+    const uint16_t* Knew;     // [B, nq, Hkv, D]
+    const uint16_t* Vnew;
+    uint16_t* Ks;             // suffix cache (packed rows or page pool)
+    uint16_t* Vs;
+    const int32_t* offsets;   // unused when pg.table != null
+    int32_t* lengths;
+    PagedDev pg;
+    int capacity;             // rows reserved per sequence
+    int B, nq;
+    int row_elems;            // Hkv * D
+};
+
 struct FillArgs {
     void* O; float* LSE; int bf16; int64_t rows; int D;
 };
@@ -96,6 +120,7 @@ bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slo
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
+hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
 
 constexpr int kPrefixRowsNarrow = 128;  // query rows per workgroup, 32-rows-per-wavefront kernel
 constexpr int kPrefixRowsWide = 256;    // query rows per workgroup, 64-rows-per-wavefront kernel

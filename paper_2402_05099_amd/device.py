@@ -82,3 +82,17 @@ def naive(ctx: hb.Context, dw: DeviceWorkload, out_dtype=torch.bfloat16, want_ls
     L = torch.empty(dw.lead, dtype=torch.float32, device=dw.Q.device) if want_lse else None
     hb.hg_naive_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
     return O, L
+
+
+def paged_to_device(pg, device="cuda:0") -> hb.PagedKV:
+    """A workloads.PagedSuffix as device tensors."""
+    return hb.PagedKV(K=bf16_tensor(pg.K, device), V=bf16_tensor(pg.V, device),
+                      page_table=torch.from_numpy(pg.table).to(device), page_size=pg.page_size)
+
+
+def hydragen_paged(ctx: hb.Context, dw: DeviceWorkload, kv: hb.PagedKV, lengths=None, max_len=None, out_dtype=torch.bfloat16):
+    O = torch.empty(dw.lead + (dw.D,), dtype=out_dtype, device=dw.Q.device)
+    L = torch.empty(dw.lead, dtype=torch.float32, device=dw.Q.device)
+    hb.hg_hydragen_attn_paged(ctx, dw.Q, dw.levels, kv, dw.lengths if lengths is None else lengths,
+                              dw.max_len if max_len is None else max_len, O, L, dw.scale)
+    return O, L

@@ -269,3 +269,68 @@ def scaled_down(idx: int, **variant) -> Workload:
     if idx == 6:
         return make_workload("c6_small", 16, 75, 8, 1, 128, [(1, 700, 75)], 50, 50, **variant)
     return config(1, **variant)
+
+
+# ---- suffix-cache layouts for the decode-step neighbours of the path (inputs only: scatter, no arithmetic) ---------
+
+@dataclass
+class PagedSuffix:
+    """The suffix rows of a workload stored in fixed-size pages of one pool (the layout Sec. 3.5 contrasts with)."""
+    K: np.ndarray          # uint16 [n_pages * page_size, Hkv, D]
+    V: np.ndarray
+    table: np.ndarray      # int32 [B, stride]: physical page of each logical page, -1 where none is assigned
+    page_size: int
+    capacity: int          # rows every sequence may hold: max_len + reserve (its pages cover at least that many)
+
+    @property
+    def n_pages(self) -> int:
+        return int(self.K.shape[0]) // self.page_size
+
+
+def make_paged(w: Workload, page_size: int, reserve: int = 0, spare_pages: int = 3, junk_gain: float = 8.0) -> PagedSuffix:
+    """Scatter w's packed suffix rows into pages handed out in a seeded random physical order.
+
+    Every sequence gets pages for max_len + reserve rows (room to append).  Rows no sequence owns (page tails,
+    reserved rows, spare pages) hold N(0,1)*junk_gain values (tensor ids 110, 111) so that a kernel that reads a
+    row it should not shows up in the result.  Table entries past a sequence's pages are -1.
+    """
+    ps = int(page_size)
+    cap = w.max_len + reserve
+    per_seq = (cap + ps - 1) // ps
+    stride = per_seq + 1
+    n_pages = w.B * per_seq + spare_pages
+    rng = np.random.default_rng(np.random.SeedSequence([w.seed, 112, ps]))
+    phys = rng.permutation(n_pages).astype(np.int32)[: w.B * per_seq].reshape(w.B, per_seq) if w.B else np.zeros((0, per_seq), np.int32)
+    table = np.full((w.B, stride), -1, dtype=np.int32)
+    table[:, :per_seq] = phys
+    K = normal_bf16(w.seed, 110, (n_pages * ps, w.Hkv, w.D), gain=junk_gain)
+    V = normal_bf16(w.seed, 111, (n_pages * ps, w.Hkv, w.D), gain=junk_gain)
+    for b in range(w.B):
+        n = int(w.lengths[b])
+        j = np.arange(n)
+        rows = phys[b, j // ps].astype(np.int64) * ps + j % ps
+        K[rows] = w.Ks[w.offsets[b]: w.offsets[b] + n]
+        V[rows] = w.Vs[w.offsets[b]: w.offsets[b] + n]
+    return PagedSuffix(K=K, V=V, table=table, page_size=ps, capacity=cap)
+
+
+def with_room(w: Workload, reserve: int, junk_gain: float = 8.0):
+    """(Ks, Vs, offsets, capacity): w's suffix re-packed so that every sequence owns max_len + reserve rows.
+
+    The rows behind a sequence's last one hold N(0,1)*junk_gain values (tensor ids 113, 114).
+    """
+    cap = w.max_len + reserve
+    Ks = normal_bf16(w.seed, 113, (w.B * cap, w.Hkv, w.D), gain=junk_gain)
+    Vs = normal_bf16(w.seed, 114, (w.B * cap, w.Hkv, w.D), gain=junk_gain)
+    offsets = (np.arange(w.B, dtype=np.int64) * cap).astype(np.int32)
+    for b in range(w.B):
+        n = int(w.lengths[b])
+        Ks[offsets[b]: offsets[b] + n] = w.Ks[w.offsets[b]: w.offsets[b] + n]
+        Vs[offsets[b]: offsets[b] + n] = w.Vs[w.offsets[b]: w.offsets[b] + n]
+    return Ks, Vs, offsets, cap
+
+
+def new_rows(w: Workload, step: int = 0):
+    """(Knew, Vnew) uint16 [B, Hkv, D] (or [B, nq, Hkv, D]): the K/V rows of the tokens a decode step adds (tensor ids 120+2*step, 121+2*step)."""
+    shape = (w.B, w.Hkv, w.D) if w.nq == 1 else (w.B, w.nq, w.Hkv, w.D)
+    return normal_bf16(w.seed, 120 + 2 * step, shape), normal_bf16(w.seed, 121 + 2 * step, shape)
