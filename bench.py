@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--prefix-kernel", type=int, default=0, help="0 auto, 1 128-row workgroups, 2 256-row workgroups")
     ap.add_argument("--paged", type=int, default=0, help="rows per page: the suffix cache is a page pool read through a page table (0 = packed rows, the default)")
     ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
+    ap.add_argument("--suffix-kernel", type=int, default=0, help="HG_OPT_SUFFIX_KERNEL: 0 automatic, 1 vector-ALU, 2 matrix-core")
     ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
     args = ap.parse_args()
 
@@ -88,6 +89,7 @@ def main() -> int:
     ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, args.prefix_kernel)
     if args.wide_slots:
         ctx.set_option(hb.HG_OPT_WIDE_SLOTS, args.wide_slots)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, args.suffix_kernel)
 
     O = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.bfloat16, device="cuda:0")
     L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")

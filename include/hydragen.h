@@ -74,7 +74,9 @@ enum {
     HG_OPT_STAGE_TIMING = 5,  /* 1: hg_hydragen_attn brackets each of its kernels with timing events */
     HG_OPT_PREFIX_KERNEL = 6, /* shared-block kernel: 0 automatic (persistent 256-row kernel for D = 128 blocks with more than 128 query rows, else the 128-row kernel), 1 always 128-row, 2 256-row wherever D = 128 */
     HG_OPT_WIDE_SLOTS = 7,    /* CUs per XCD (1..32) that the persistent 256-row kernel occupies; 0 = automatic */
-    HG_OPT_NUM_QUERIES = 8    /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
+    HG_OPT_NUM_QUERIES = 8,   /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
+    HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10, /* matrix-core suffix kernel: consecutive work items one wavefront takes (1..1024; 0 = automatic) */
+    HG_OPT_SUFFIX_KERNEL = 9  /* suffix kernel: 0 automatic (matrix-core kernel when D = 128, the rows are packed and a KV head serves >= 4 query rows of a sequence; else the vector-ALU kernel), 1 always vector-ALU, 2 matrix-core wherever D = 128 and the rows are packed */
 };
 enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };
 

@@ -19,6 +19,8 @@ HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING, HG_OPT_PREFIX_KERNEL = 1, 2, 3, 4, 5, 6
 HG_OPT_WIDE_SLOTS = 7
 HG_OPT_NUM_QUERIES = 8
+HG_OPT_SUFFIX_KERNEL = 9
+HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)

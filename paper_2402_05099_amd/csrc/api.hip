@@ -1,6 +1,7 @@
 // Host side of libhydragen: argument checks, work partitioning, kernel sequencing.  No device allocation,
 // no host synchronisation, no copies: every entry point only enqueues kernels on the context's stream.
 #include <math.h>
+#include <algorithm>
 #include <new>
 
 #include "hg_internal.h"
@@ -17,6 +18,8 @@ struct hg_ctx {
     int opt_prefix_kernel;
     int opt_wide_slots;
     int opt_nq;            // queries per sequence (1 = decode)
+    int opt_suffix_kernel; // 0 automatic, 1 vector-ALU kernel, 2 matrix-core kernel wherever it applies
+    int opt_suffix_ipw;    // matrix-core suffix kernel: work items per wavefront (0 automatic)
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -160,30 +163,44 @@ int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int nq, 
     return hip_rc(launch_prefix_narrow(a, D, s));
 }
 
-struct SuffixPlan { int chunk, nchunks, gt; };
+struct SuffixPlan { int chunk, nchunks, gt; bool mfma; int ipw; };
 
-// Work items of the suffix kernel are (sequence, KV head, group of query heads, key chunk), one wavefront each.
+// Work items of the suffix kernel are (sequence, query, KV head, group of query heads, key chunk), one wavefront
+// each, in the vector-ALU kernel, and (sequence, KV head, 32-row tile of the nq * G rows, key chunk) in the
+// matrix-core kernel.  The matrix-core kernel (D = 128, packed rows) takes over when a KV head serves four or more
+// query rows of a sequence (grouped-query attention, several queries per sequence): the vector-ALU kernel is then
+// bound by its dot products, not by HBM, and re-reads the suffix once per query.  HG_OPT_SUFFIX_KERNEL forces either.
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
 // max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int Hkv, int max_chunk = 1 << 30) {
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30) {
     SuffixPlan p;
     p.gt = pick_gt(G);
+    const int R = nq * G;
+    p.ipw = c->opt_suffix_ipw;
+    p.mfma = D == 128 && !paged && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
         if (p.chunk > max_chunk) p.chunk = max_chunk;
+    } else if (p.mfma) {
+        // a wavefront pays a fixed price per work item (its query tile, the first stage's latency, the result's
+        // stores): long items, cut only when there would be fewer than three per CU
+        p.chunk = 1024;
+        const long long per_chunk = (long long)B * Hkv * ceil_div(R, 32);
+        while (p.chunk > 128 && per_chunk * ceil_div(max_len > 0 ? max_len : 1, p.chunk) < 768) p.chunk /= 2;
     } else {
         p.chunk = 256;
-        const long long per_chunk = (long long)B * Hkv * (G / p.gt);
+        const long long per_chunk = (long long)B * nq * Hkv * (G / p.gt);
         while (p.chunk > 64 && per_chunk * ceil_div(max_len > 0 ? max_len : 1, p.chunk) < 2048) p.chunk /= 2;
     }
+    if (p.chunk > max_chunk) p.chunk = max_chunk;
     p.nchunks = max_len > 0 ? ceil_div(max_len, p.chunk) : 1;
     return p;
 }
 
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
                const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
-               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}) {
+               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0) {
     DecodeArgs a{};
     a.pg = pg;
     a.Q = static_cast<const uint16_t*>(Q);
@@ -201,6 +218,15 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
     a.units = (int64_t)B * nq * nchunks * Hkv * (a.G / gt);
     a.scale = scale;
     a.out = out;
+    if (mfma) {
+        const int64_t items = (int64_t)B * nchunks * ceil_div(nq * a.G, 32) * Hkv;
+        if (items >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+        a.items = (int)items;
+        // consecutive items per wavefront: the copies of the next item are in flight while one is finished; few
+        // enough per wavefront that the hardware still balances ragged lengths (>= 8 workgroups per resident slot)
+        a.ipw = mfma_ipw > 0 ? mfma_ipw : (int)std::min<int64_t>(4, std::max<int64_t>(1, items / (1280 * 8)));
+        return hip_rc(launch_decode_mfma(a, s));
+    }
     return hip_rc(launch_decode(a, D, gt, s));
 }
 
@@ -292,6 +318,8 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->ws_bytes = workspace_bytes;
     c->opt_prefix_splits = c->opt_suffix_chunk = c->opt_overlap = c->opt_naive_chunk = c->opt_prefix_kernel = c->opt_wide_slots = 0;
     c->opt_nq = 1;
+    c->opt_suffix_kernel = 0;
+    c->opt_suffix_ipw = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -345,6 +373,14 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_NUM_QUERIES:
             if (value < 1 || value > 64) return HG_ERR_INVALID_ARG;
             c->opt_nq = value;
+            return HG_OK;
+        case HG_OPT_SUFFIX_KERNEL:
+            if (value > 2) return HG_ERR_INVALID_ARG;
+            c->opt_suffix_kernel = value;
+            return HG_OK;
+        case HG_OPT_SUFFIX_ITEMS_PER_WAVE:
+            if (value > 1024) return HG_ERR_INVALID_ARG;
+            c->opt_suffix_ipw = value;
             return HG_OK;
         case HG_OPT_WIDE_SLOTS:
             if (value > 32) return HG_ERR_INVALID_ARG;
@@ -434,7 +470,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B * nq, Hkv, max_chunk);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
@@ -443,9 +479,9 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (p.chunk > max_chunk) return HG_ERR_WORKSPACE;
     if (p.nchunks == 1)
         return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
-                          direct_out(O, o_dtype, LSE), s, pg);
+                          direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw);
     rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
-                    parts_out(parts, 0), s, pg);
+                    parts_out(parts, 0), s, pg, p.mfma, p.ipw);
     if (rc) return rc;
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
 }
@@ -565,7 +601,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         ++nlev;
     }
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan sp = plan_suffix(c, max_len, G, B * nq, Hkv, max_chunk);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
@@ -624,7 +660,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
         const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, sp.chunk,
-                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg);
+                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg, sp.mfma, sp.ipw);
         if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;

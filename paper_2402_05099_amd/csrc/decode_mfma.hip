@@ -1,0 +1,447 @@
+// Suffix attention on the matrix cores (Sec. 3.2, last paragraph; App. B with num_queries >= 1), D = 128, packed
+// suffix rows.  The per-sequence part of Hydragen is a matrix-vector product only while one KV head serves one
+// query row; with grouped-query attention and with several queries per sequence a KV head serves R = nq * G rows,
+// and the vector-ALU kernel (decode.hip) then pays R dot products per key and, across queries, re-reads the
+// suffix.  Here a work item is (sequence, KV head, 32-row tile of the R rows, key chunk): every K/V row is read
+// once and multiplied on v_mfma_f32_32x32x16_bf16 exactly as in the shared-block kernels (transposed products
+// S^T = K Q^T, O^T += V^T P^T, a lane owns one query row, lazy rescaling); rows past R idle in the tile, which costs
+// nothing because the kernel is bound by HBM, not by the matrix cores.
+//
+// A workgroup is ONE wavefront that takes a few consecutive work items and streams them through a ring of NS
+// 16 KiB slots private to it: per item one Q element (the query tile) and then its K/V stages of 32 keys, copied
+// HBM -> LDS by global_load_lds_dwordx4 with the same XOR swizzles as prefix_wide.hip, always NS-1 elements ahead
+// of the one being consumed, across item boundaries.  The copies are issued from inline asm and waited for with
+// counted s_waitcnt vmcnt (the compiler would otherwise drain every copy before each LDS read), so the kernel
+// contains no vector load that the compiler can see: lengths and offsets come through scalar loads.  No barrier
+// anywhere.  160 KiB / (NS * 16 KiB) wavefronts share a CU (NS = 2: five).
+//
+// Several queries per sequence: row r of a sequence's R rows is (query t, head g) = (r / G, r % G); query t sees
+// suffix rows [0, length - (nq-1-t)), applied as a per-lane bound on the key index in the stages that reach it.
+#include "hg_internal.h"
+#include "prefix_common.h"
+
+#pragma clang diagnostic ignored "-Winline-asm"
+
+namespace hg {
+
+namespace {
+
+constexpr int D = 128;
+constexpr int KT = 32;                  // keys per stage
+constexpr int KS = D / 16;              // MFMA k-steps of the score product
+constexpr int DB = D / 32;              // 32-row blocks of O^T
+constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
+constexpr int RPI = 64 / CPR;           // rows one copy instruction covers
+constexpr int CPS = KT / RPI;           // copy instructions per stage and tensor
+constexpr int ROWB = D * 2;             // bytes per row
+constexpr int STB = KT * ROWB;          // bytes per stage and tensor
+constexpr float TAU = 8.0f;             // lazy-rescale threshold, log2 units
+
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned pack_pair(float lo, float hi) {
+    floatx2 f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+
+extern __shared__ __attribute__((aligned(1024))) unsigned char dm_smem[];
+
+// s_waitcnt vmcnt(n) alone (lgkmcnt and expcnt untouched): vmcnt is split over bits [3:0] and [15:14]
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+}  // namespace
+
+template <int NS>
+__global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
+    static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
+    constexpr int VRING = NS * STB;
+    constexpr int QOPS = CPS, KVOPS = 2 * CPS;     // copy instructions per ring element
+    unsigned char* const smem = dm_smem;
+    const int l = threadIdx.x, lq = l & 31, hl = l >> 5;
+    const int R = a.nq * a.G;
+    const int RT = (R + 31) >> 5;
+    const int item0 = blockIdx.x * a.ipw;
+    const int item1 = min(item0 + a.ipw, a.items);
+
+    // lengths and offsets are read through the constant address space: nothing writes them while the kernel runs, and
+    // the compiler then keeps these loads on the scalar unit (a vector load here would make it wait for vmcnt(0),
+    // which drains every copy in flight)
+    typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+    const const_i32_ptr lengths_c = (const_i32_ptr)(uintptr_t)a.lengths;
+    const const_i32_ptr offsets_c = (const_i32_ptr)(uintptr_t)a.offsets;
+
+    // One work item: (sequence b, key chunk c, 32-row tile rt, KV head kvh), adjacent items on adjacent KV heads.
+    // Everything here is wavefront-uniform.
+    struct Item {
+        int b, c, rt, kvh;
+        int off, count;      // first suffix row of the sequence in Ks/Vs; suffix rows the newest query sees
+        int ks, ke;          // absolute rows [ks, ke) of this item's keys (empty: ks >= ke)
+        int kwin, nst;
+    };
+    // (b, c, rt, kvh) of item i; integer division runs on the vector unit, readfirstlane brings the (uniform) results
+    // back to scalar registers.  Used once per wavefront: the cursors then step from item to item.
+    auto index_of = [&](int i, Item& it) {
+        int u = i;
+        it.kvh = __builtin_amdgcn_readfirstlane(u % a.Hkv); u = __builtin_amdgcn_readfirstlane(u / a.Hkv);
+        it.rt = __builtin_amdgcn_readfirstlane(u % RT); u = __builtin_amdgcn_readfirstlane(u / RT);
+        it.c = __builtin_amdgcn_readfirstlane(u % a.nchunks);
+        it.b = __builtin_amdgcn_readfirstlane(u / a.nchunks);
+    };
+    auto next_index = [&](Item& it) {
+        if (++it.kvh == a.Hkv) {
+            it.kvh = 0;
+            if (++it.rt == RT) {
+                it.rt = 0;
+                if (++it.c == a.nchunks) { it.c = 0; ++it.b; }
+            }
+        }
+    };
+    // key range of the item whose index fields are set
+    auto range_of = [&](Item& it) {
+        it.count = __builtin_amdgcn_readfirstlane(max(min(lengths_c[it.b], a.max_len), 0));
+        it.off = __builtin_amdgcn_readfirstlane(offsets_c[it.b]);
+        const int lo = it.c * a.chunk, hi = min(lo + a.chunk, it.count);
+        it.ks = __builtin_amdgcn_readfirstlane(it.off + lo);
+        it.ke = __builtin_amdgcn_readfirstlane(it.off + max(hi, lo));
+        it.kwin = max(it.ke - KT, 0);
+        it.nst = (it.ke - it.ks + KT - 1) / KT;
+    };
+
+    // ---- HBM -> LDS copies -------------------------------------------------------------------------------------------
+    // A wavefront streams a sequence of ring elements: for every non-empty item one Q element (the 32 query rows of
+    // the tile, 8 copy instructions) followed by its K/V stages (32 keys, 16 copy instructions), element n in slot
+    // n % NS, NS-1 elements ahead of the one being consumed, across item boundaries.  All copies are 1 KiB
+    // global_load_lds_dwordx4 issued from inline asm (the compiler must not see them: it would drain them all before
+    // every LDS read) and are waited for with counted s_waitcnt vmcnt; loads return in order, so "at most the copies
+    // of the younger elements are outstanding" means the current element has landed.  The output stores in between
+    // also count in vmcnt and may complete out of order with loads: they can only make a wait longer, never shorter.
+    //
+    // K/V stage t of an item holds rows [k0c, k0c + 32), k0c = min(ks + 32 t, kwin), kwin = max(ke - 32, 0): a partial
+    // last stage re-reads the 32 rows that end the range (rows before ks belong to an earlier chunk or sequence and
+    // are masked), so every copy has the same shape; row i of a stage is a key of it iff ks + 32 t <= k0c + i < ke.
+    // 16-byte chunks are XOR-swizzled on the global side (K and Q: chunk ^ row % 16, V: chunk ^ 4 (row % 4)).
+    const unsigned rstride_b = (unsigned)a.Hkv * D * 2u;
+    const int lrow = l / CPR, sch = l % CPR;
+    const unsigned ldsb = (unsigned)(uintptr_t)HG_LDS(smem);
+    // base pointers and LDS addresses are wavefront-uniform; readfirstlane puts them in scalar registers even where
+    // the compiler computed them with vector instructions (64-bit multiplies)
+    auto copy16 = [&](const unsigned char* vbase, unsigned voff, unsigned vdst) {
+        const uint64_t pv = reinterpret_cast<uint64_t>(vbase);
+        // readfirstlane returns a signed int: both halves go through uint32_t so that the low half is not sign-extended
+        const uint32_t plo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)pv);
+        const uint32_t phi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(pv >> 32));
+        const unsigned char* const sbase = reinterpret_cast<const unsigned char*>(((uint64_t)phi << 32) | (uint64_t)plo);
+        const unsigned lds_dst = __builtin_amdgcn_readfirstlane(vdst);
+#ifndef HG_DM_POLICY
+#define HG_DM_POLICY " nt"
+#endif
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" HG_DM_POLICY ::"v"(voff), "s"(sbase), "s"(lds_dst) : "memory", "m0");
+    };
+
+    // ---- LDS fragment addresses (relative to the slot), as in prefix_wide.hip ------------------------------------------
+    unsigned kaddr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    unsigned vaddr[DB];
+    {
+        const int i16 = l & 15, g1 = (l >> 4) & 1;
+        const int keyq = 4 * hl + (i16 >> 2);
+        const int fv = 4 * (keyq % 4);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);
+            vaddr[db] = (unsigned)(VRING + keyq * ROWB + ((chunk ^ fv) * 16) + (i16 & 1) * 8);
+        }
+    }
+
+    // ---- producer: runs NS-1 elements ahead of the consumer ----------------------------------------------------------------
+    int p_item = item0, p_el = -1;     // next element to issue: element -1 of an item is its Q tile
+    int n_issued = 0;                  // elements issued so far (element n lives in slot n % NS)
+    int pending = 0;                   // copy instructions of the elements issued and not yet consumed
+    Item pit{};
+    unsigned voffK[CPS], voffV[CPS], voffQ[CPS];   // lane offsets of the producer's item: K/V stage rows, Q tile rows
+    int voff_clamp = -1, voff_rt = -1;             // the row clamp / row tile these offsets were computed for
+    // position the producer on the next item that has keys and set up its lane offsets
+    auto p_load = [&](bool first) {
+        if (p_item >= item1) return;
+        if (first) index_of(p_item, pit);
+        else next_index(pit);
+        while (true) {
+            range_of(pit);
+            if (pit.ks < pit.ke) break;
+            if (++p_item >= item1) return;
+            next_index(pit);
+        }
+        const int rowclamp = min(pit.ke - 1 - pit.kwin, KT - 1);   // < 31 only when the range ends before row 32 of the tensor
+        if (rowclamp != voff_clamp) {
+            voff_clamp = rowclamp;
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) {
+                const int srow = i * RPI + lrow;
+                const unsigned ro = (unsigned)min(srow, rowclamp) * rstride_b;
+                voffK[i] = ro + (unsigned)((sch ^ (srow % CPR)) * 16);
+                voffV[i] = ro + (unsigned)((sch ^ (4 * (srow % 4))) * 16);
+            }
+        }
+        if (pit.rt != voff_rt) {
+            voff_rt = pit.rt;
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) {
+                const int srow = i * RPI + lrow;
+                int r = pit.rt * 32 + srow;                 // Q tile row i is query row rt*32 + i of (b, kvh); row 0 when past R
+                if (r >= R) r = 0;
+                voffQ[i] = (unsigned)((r / a.G) * a.Hq + r % a.G) * ROWB + (unsigned)((sch ^ (srow % CPR)) * 16);
+            }
+        }
+    };
+    auto produce_one = [&]() {
+        p_item = __builtin_amdgcn_readfirstlane(p_item);
+        p_el = __builtin_amdgcn_readfirstlane(p_el);
+        n_issued = __builtin_amdgcn_readfirstlane(n_issued);
+        pending = __builtin_amdgcn_readfirstlane(pending);
+        if (p_item >= item1) return;
+        const unsigned dst = ldsb + (unsigned)(n_issued % NS) * STB;
+        if (p_el < 0) {
+            const unsigned char* const qg = reinterpret_cast<const unsigned char*>(a.Q + ((int64_t)pit.b * a.nq * a.Hq + pit.kvh * a.G) * D);
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) copy16(qg, voffQ[i], dst + i * (RPI * ROWB));
+            pending += QOPS;
+        } else {
+            const int k0c = min(pit.ks + p_el * KT, pit.kwin);
+            const int64_t goff = (int64_t)k0c * rstride_b + (int64_t)pit.kvh * ROWB;
+            const unsigned char* const kg = reinterpret_cast<const unsigned char*>(a.Ks) + goff;
+            const unsigned char* const vg = reinterpret_cast<const unsigned char*>(a.Vs) + goff;
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) copy16(kg, voffK[i], dst + i * (RPI * ROWB));
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) copy16(vg, voffV[i], dst + VRING + i * (RPI * ROWB));
+            pending += KVOPS;
+        }
+        ++n_issued;
+        if (++p_el == pit.nst) {
+            p_el = -1;
+            ++p_item;
+            p_load(false);
+        }
+    };
+    // wait until at most `younger` copy instructions are outstanding (a multiple of CPS, at most (NS-1) * KVOPS)
+    auto wait_for = [&](int younger) {
+        switch (younger / CPS) {
+            case 0: wait_vm<0>(); break;
+            case 1: wait_vm<1 * CPS>(); break;
+            case 2: wait_vm<2 * CPS>(); break;
+            case 3: wait_vm<3 * CPS>(); break;
+            case 4: wait_vm<4 * CPS>(); break;
+            case 5: wait_vm<5 * CPS>(); break;
+            case 6: wait_vm<6 * CPS>(); break;
+            default: wait_vm<0>(); break;
+        }
+        asm volatile("" ::: "memory");
+    };
+    p_load(true);
+#pragma nounroll
+    for (int s = 0; s < NS - 1; ++s) produce_one();
+
+    // ---- consumer ---------------------------------------------------------------------------------------------------------
+    const float c2 = a.scale * kLog2e;
+    const float tau_raw = TAU / c2;
+    int c_item = item0, c_el = -1, n_done = 0;
+    Item cit{};
+    // lane state of the consumer's item
+    bool rv = false;
+    int64_t qidx = 0;
+    int vis_end = 0, causal_from = 0;
+    bf16x8 qf[KS];
+    floatx16 Oacc[DB];
+    float m_used = -INFINITY;   // raw-score maximum the exponentials are taken against (-inf: no key seen yet)
+    float mc = 0.f;             // m_used * c2, 0 while no key has been seen
+    float lsum = 0.f;           // this lane's share of the row sum (unrounded exponentials)
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, uintx4{0, 0, 0, 0});
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) Oacc[i][k] = 0.f;
+
+    int lane_rt = -1, lane_tq = 0, lane_g = 0;   // (query, head in the group) of this lane's row, for row tile lane_rt
+    auto lane_of = [&](const Item& it) {
+        if (it.rt != lane_rt) {
+            lane_rt = it.rt;
+            const int r = it.rt * 32 + lq;    // this lane's row among the R rows of (b, kvh)
+            rv = r < R;
+            const int rr = rv ? r : 0;
+            lane_tq = rr / a.G;
+            lane_g = rr % a.G;
+        }
+        qidx = ((int64_t)it.b * a.nq + lane_tq) * a.Hq + it.kvh * a.G + lane_g;
+        vis_end = it.off + it.count - (a.nq - 1 - lane_tq);   // this lane's query sees absolute rows below vis_end
+        causal_from = it.off + it.count - (a.nq - 1);         // below this row every query sees every key
+    };
+    // position the consumer on the next item that has keys; items without keys get the empty part on the way
+    auto c_load = [&](bool first) {
+        if (c_item >= item1) return;
+        if (first) index_of(c_item, cit);
+        else next_index(cit);
+        while (true) {
+            range_of(cit);
+            if (cit.ks < cit.ke) break;
+            lane_of(cit);
+            if (rv) {
+                float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+#pragma unroll
+                for (int i = 0; i < D / 8; ++i) {
+                    const int d = 8 * i + 4 * hl;
+                    if (a.out.bf16) *reinterpret_cast<uint2*>(Ob + d) = make_uint2(0u, 0u);
+                    else *reinterpret_cast<float4*>(Of + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                if (hl == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = -INFINITY;
+            }
+            if (++c_item >= item1) return;
+            next_index(cit);
+        }
+    };
+    c_load(true);
+
+    while (c_item < item1) {
+        c_item = __builtin_amdgcn_readfirstlane(c_item);
+        c_el = __builtin_amdgcn_readfirstlane(c_el);
+        n_done = __builtin_amdgcn_readfirstlane(n_done);
+        produce_one();          // refills the slot of the element consumed last (its fragment reads have completed)
+        const unsigned char* const sb = smem + (n_done % NS) * STB;
+        ++n_done;
+        if (c_el < 0) {
+            // Q element -> registers; fresh softmax state
+            pending -= QOPS;
+            wait_for(pending);
+            lane_of(cit);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + kaddr[s]));
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int k = 0; k < 16; ++k) Oacc[i][k] = 0.f;
+            m_used = -INFINITY;
+            mc = 0.f;
+            lsum = 0.f;
+            // the fragments must be in registers before a later copy may overwrite this slot
+#pragma unroll
+            for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[s]));
+            asm volatile("" ::: "memory");
+        } else {
+            pending -= KVOPS;
+            wait_for(pending);
+            // S^T = K Q^T
+            floatx16 S;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uintx4 kv = *reinterpret_cast<const uintx4*>(sb + kaddr[s]);
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S, 0, 0, 0);
+            }
+            // keys outside [key0, min(ke, vis_end)): stage rows before the stage's first key (window clamp), rows past
+            // the range, and rows that this lane's query does not see yet
+            const int key0 = cit.ks + c_el * KT;
+            const int k0c = min(key0, cit.kwin);
+            if (k0c != key0 || key0 + KT > cit.ke || key0 + KT > causal_from) {
+                const int lo_i = key0 - k0c - 4 * hl, hi_i = min(cit.ke, vis_end) - k0c - 4 * hl;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int ri = 8 * (i >> 2) + (i & 3);   // stage row of element i is ri + 4*hl
+                    if (ri < lo_i || ri >= hi_i) S[i] = -INFINITY;
+                }
+            }
+            float tmax = fmaxf(S[0], S[1]);
+#pragma unroll
+            for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, S[i]), S[i + 1]);
+            tmax = half_max(tmax);
+            if (__any(tmax > m_used + tau_raw)) {
+                const float m_new = fmaxf(m_used, tmax);
+                // equal maxima (also -inf and -inf: a row that has seen no key yet) keep the accumulators
+                const float alpha = (m_new == m_used) ? 1.0f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
+                m_used = m_new;
+                mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+                lsum *= alpha;
+#pragma unroll
+                for (int i = 0; i < DB; ++i)
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) Oacc[i][k] *= alpha;
+            }
+            // P^T = 2^(S*c2 - m*c2), packed to bf16 in B-operand order (elements 8*tt .. 8*tt+7 are the k-slots of key half tt)
+            uintx4 pb[2];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                float p[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    p[i] = __builtin_amdgcn_exp2f(fmaf(S[8 * tt + i], c2, -mc));
+                    lsum += p[i];
+                }
+                pb[tt] = uintx4{pack_pair(p[0], p[1]), pack_pair(p[2], p[3]), pack_pair(p[4], p[5]), pack_pair(p[6], p[7])};
+            }
+            // O^T += V^T P^T
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const unsigned char* vp = sb + vaddr[db] + tt * 16 * ROWB;
+                    const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                    const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
+                    const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                }
+            }
+            // the accumulators depend on every fragment read of this step: once they are pinned here the reads have
+            // completed, and the next produce_one() may overwrite the slot
+#pragma unroll
+            for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(Oacc[db]));
+            asm volatile("" ::: "memory");
+        }
+        if (++c_el == cit.nst) {
+            // last stage of the item: write (O, LSE) of the part
+            const float ltot = half_sum(lsum);
+            if (rv) {
+                float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;    // a row that sees no key of this chunk: O = 0, LSE = -inf
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const int d = 32 * db + 8 * q4 + 4 * hl;
+                        const float o0 = Oacc[db][4 * q4] * inv, o1 = Oacc[db][4 * q4 + 1] * inv;
+                        const float o2 = Oacc[db][4 * q4 + 2] * inv, o3 = Oacc[db][4 * q4 + 3] * inv;
+                        if (a.out.bf16) *reinterpret_cast<uint2*>(Ob + d) = make_uint2(pack_bf16(o0, o1), pack_bf16(o2, o3));
+                        else *reinterpret_cast<float4*>(Of + d) = make_float4(o0, o1, o2, o3);
+                    }
+                }
+                if (hl == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = ltot > 0.f ? m_used * a.scale + __logf(ltot) : -INFINITY;
+            }
+            c_el = -1;
+            ++c_item;
+            c_load(false);
+        }
+    }
+}
+
+// Work items: B * nchunks * ceil(nq*G / 32) * Hkv, adjacent ids on adjacent KV heads of the same rows; a.ipw
+// consecutive items per wavefront (= workgroup).
+hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
+#ifndef HG_DM_NS
+#define HG_DM_NS 2
+#endif
+    constexpr int NS = HG_DM_NS;
+    if (a.items == 0) return hipSuccess;
+    if (a.ipw < 1 || a.n_levels != 0 || a.pg.table != nullptr) return hipErrorInvalidValue;
+    const int grid = (a.items + a.ipw - 1) / a.ipw;
+    decode_mfma_kernel<NS><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace hg

@@ -40,7 +40,8 @@ def test_paged_suffix_attn(idx, page_size):
     hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
     torch.cuda.synchronize()
     check(to_np(O), to_np(L), Oref, Lref, f"paged suffix idx={idx} ps={page_size}")
-    # the packed cache holds the same rows and is walked in the same order: identical bits
+    # the packed cache holds the same rows and the same (vector-ALU) kernel walks them in the same order: identical bits
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, 1)
     O2, L2 = torch.empty_like(O), torch.empty_like(L)
     hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O2, L2, dw.scale)
     torch.cuda.synchronize()

@@ -91,6 +91,47 @@ def test_suffix_attn(idx, chunk):
     ctx.close()
 
 
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4], ids=["valu", "mfma", "mfma_ipw3", "mfma_ipw1000"])
+@pytest.mark.parametrize("chunk", [0, 32, 96])
+@pytest.mark.parametrize("case", ["mha", "gqa8", "gqa4_nq3", "mha_nq5", "gqa8_nq7_two_row_tiles", "long"])
+def test_suffix_kernels(case, chunk, kernel):
+    """Both suffix kernels (vector-ALU, matrix-core) on every shape class: one row per KV head, grouped heads, several
+    queries per sequence (causal tail, suffixes shorter than the query block), more than 32 rows per KV head, and
+    suffixes of several hundred rows cut into chunks that start and end inside 32-key stages."""
+    say(f"suffix kernels {case} chunk={chunk} kernel={kernel}")
+    rng = np.random.default_rng(len(case))
+    def lens(B, hi, nq):
+        ln = rng.integers(0, hi + 1, size=B).astype(np.int32)
+        ln[:6] = [0, 1, max(nq - 1, 0), nq, 31, 33]
+        return ln
+    if case == "mha":
+        w = wl.make_workload(case, 81, 29, 4, 4, 128, [], 0, 0, lengths=lens(29, 150, 1))
+    elif case == "gqa8":
+        w = wl.make_workload(case, 82, 23, 16, 2, 128, [], 0, 0, lengths=lens(23, 200, 1))
+    elif case == "gqa4_nq3":
+        w = wl.make_workload(case, 83, 19, 8, 2, 128, [], 0, 0, lengths=lens(19, 120, 3), nq=3)
+    elif case == "mha_nq5":
+        w = wl.make_workload(case, 84, 17, 4, 4, 128, [], 0, 0, lengths=lens(17, 100, 5), nq=5)
+    elif case == "gqa8_nq7_two_row_tiles":   # 56 rows per KV head: two 32-row tiles, the second half empty
+        w = wl.make_workload(case, 85, 11, 8, 1, 128, [], 0, 0, lengths=lens(11, 90, 7), nq=7)
+    else:
+        w = wl.make_workload(case, 86, 9, 8, 2, 128, [], 0, 0, lengths=lens(9, 700, 1))
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, min(kernel, 2))
+    if kernel > 2:   # several work items per wavefront: copies of the next item are in flight while one finishes
+        ctx.set_option(hb.HG_OPT_SUFFIX_ITEMS_PER_WAVE, 3 if kernel == 3 else 1000)
+    if chunk:
+        ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
+    Oref, Lref = oracle.attention(w)
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"suffix {case} kernel={kernel} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
 @pytest.mark.parametrize("idx", [1, 2, 3, 4])
 @pytest.mark.parametrize("splits", [0, 1, 3])
 @pytest.mark.parametrize("kernel", [1, 2], ids=["rows128", "rows256"])
