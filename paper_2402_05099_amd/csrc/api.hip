@@ -273,11 +273,11 @@ int pick_wide_slots(double flops, double bytes, int T) {
     const double ts = bytes / bw, tp32 = flops / full_rate;
     if (ts >= 2.0 * tp32) {
         // the suffix kernel dominates: the fewest CUs on which the shared blocks still finish in half its time
-        for (int s = 4; s <= 32; s += 4) {
+        // (when teams are so wide that no smaller count does, the general model below decides)
+        for (int s = 4; s < 32; s += 4) {
             const int eff = s / T * T;
             if (eff >= 4 && flops / (full_rate * rate_at(eff)) <= 0.5 * ts) return s;
         }
-        return 32;
     }
     int best = 32;
     double best_t = 1e30;
@@ -287,7 +287,7 @@ int pick_wide_slots(double flops, double bytes, int T) {
         const double tp = flops / (full_rate * rate_at(eff));
         const double conc = 0.7 * bw * (256 - 8 * eff) / 256.0;
         const double t = bytes <= conc * tp ? tp : tp + (bytes - conc * tp) / bw;
-        if (t < best_t * 0.98) { best_t = t; best = s; }
+        if (t < best_t * 0.995) { best_t = t; best = s; }
     }
     return best;
 }

@@ -128,15 +128,17 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
     const unsigned rstride_b = (unsigned)a.Hkv * D * 2u;
     const int lrow = l / CPR, sch = l % CPR;
     const unsigned ldsb = (unsigned)(uintptr_t)HG_LDS(smem);
-    // base pointers and LDS addresses are wavefront-uniform; readfirstlane puts them in scalar registers even where
-    // the compiler computed them with vector instructions (64-bit multiplies)
-    auto copy16 = [&](const unsigned char* vbase, unsigned voff, unsigned vdst) {
+    // Base pointers and LDS addresses are wavefront-uniform; readfirstlane puts them in scalar registers even where
+    // the compiler computed them with vector instructions (64-bit multiplies).  Done once per ring element: a copy
+    // is then s_add, s_mov m0 and the load.
+    auto scalar_ptr = [&](const unsigned char* vbase) -> const unsigned char* {
         const uint64_t pv = reinterpret_cast<uint64_t>(vbase);
         // readfirstlane returns a signed int: both halves go through uint32_t so that the low half is not sign-extended
         const uint32_t plo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)pv);
         const uint32_t phi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(pv >> 32));
-        const unsigned char* const sbase = reinterpret_cast<const unsigned char*>(((uint64_t)phi << 32) | (uint64_t)plo);
-        const unsigned lds_dst = __builtin_amdgcn_readfirstlane(vdst);
+        return reinterpret_cast<const unsigned char*>(((uint64_t)phi << 32) | (uint64_t)plo);
+    };
+    auto copy16 = [&](const unsigned char* sbase, unsigned voff, unsigned lds_dst) {
 #ifndef HG_DM_POLICY
 #define HG_DM_POLICY " nt"
 #endif
@@ -205,17 +207,17 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
         n_issued = __builtin_amdgcn_readfirstlane(n_issued);
         pending = __builtin_amdgcn_readfirstlane(pending);
         if (p_item >= item1) return;
-        const unsigned dst = ldsb + (unsigned)(n_issued % NS) * STB;
+        const unsigned dst = (unsigned)__builtin_amdgcn_readfirstlane(ldsb + (unsigned)(n_issued % NS) * STB);
         if (p_el < 0) {
-            const unsigned char* const qg = reinterpret_cast<const unsigned char*>(a.Q + ((int64_t)pit.b * a.nq * a.Hq + pit.kvh * a.G) * D);
+            const unsigned char* const qg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Q + ((int64_t)pit.b * a.nq * a.Hq + pit.kvh * a.G) * D));
 #pragma unroll
             for (int i = 0; i < CPS; ++i) copy16(qg, voffQ[i], dst + i * (RPI * ROWB));
             pending += QOPS;
         } else {
             const int k0c = min(pit.ks + p_el * KT, pit.kwin);
             const int64_t goff = (int64_t)k0c * rstride_b + (int64_t)pit.kvh * ROWB;
-            const unsigned char* const kg = reinterpret_cast<const unsigned char*>(a.Ks) + goff;
-            const unsigned char* const vg = reinterpret_cast<const unsigned char*>(a.Vs) + goff;
+            const unsigned char* const kg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Ks) + goff);
+            const unsigned char* const vg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Vs) + goff);
 #pragma unroll
             for (int i = 0; i < CPS; ++i) copy16(kg, voffK[i], dst + i * (RPI * ROWB));
 #pragma unroll
