@@ -15,7 +15,7 @@ from parity import check, to_np
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("idx", [3, 5])
+@pytest.mark.parametrize("idx", [3, 4, 5])
 def test_fused_call_captured_in_a_graph_and_replayed(idx):
     print(f"graph capture idx={idx}", file=sys.stderr, flush=True)
     w = wl.scaled_down(idx)
