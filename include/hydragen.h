@@ -112,7 +112,9 @@ int hg_prefix_attn(hg_ctx* ctx, const void* Q, const void* Kp, const void* Vp,
  * Block g owns KV rows [kv_off[g], kv_off[g+1]) and is attended to by the contiguous sequences
  * [seq_off[g], seq_off[g+1]) (sequences are in tree order).  kv_off/seq_off are DEVICE int32[n_blocks+1],
  * non-decreasing.  max_rows / max_seqs are host upper bounds on rows and sequences per block; a block
- * exceeding them is truncated.  With n_blocks == 1 both arrays may be NULL: the block is then rows
+ * exceeding them is truncated.  A block shorter than 32 rows is read together with the rows stored just below it
+ * (they get weight zero): those rows must hold finite values, which blocks stored back to back guarantee.
+ * With n_blocks == 1 both arrays may be NULL: the block is then rows
  * [0, max_rows) shared by sequences [0, B).  Sequences not covered by any block get O = 0, LSE = -inf.
  */
 typedef struct {
@@ -133,7 +135,8 @@ int hg_prefix_attn_grouped(hg_ctx* ctx, const void* Q, const hg_level* level,
  * Per-sequence attention over ragged suffix KV (Sec. 3.2, last paragraph).  Sequence b owns rows
  * [offsets[b], offsets[b] + lengths[b]) of Ks/Vs (bf16 [T, Hkv, D]); offsets/lengths are DEVICE int32[B];
  * a padded [B, Lmax, Hkv, D] cache is offsets[b] = b * Lmax.  lengths[b] == 0 is legal; lengths above
- * max_len (a host upper bound) are truncated to max_len.
+ * max_len (a host upper bound) are truncated to max_len.  Rows of Ks/Vs that no sequence owns (padding, slots of
+ * empty sequences) may hold anything, NaN included: they are never given a weight and never reach a result.
  */
 int hg_suffix_attn(hg_ctx* ctx, const void* Q, const void* Ks, const void* Vs,
                    const int32_t* offsets, const int32_t* lengths, int max_len,

@@ -359,6 +359,18 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
                     if (ri < lo_i || ri >= hi_i) S[i] = -INFINITY;
                 }
             }
+            if (k0c != key0) {
+                // The stage rows before its first key were re-read from below the range: they may lie in another
+                // sequence's slot of the cache, possibly padding that was never written.  Their probabilities are
+                // zero, but 0 * NaN is NaN in the second product: clear those V rows in LDS.
+                const int nlo = key0 - k0c;
+                unsigned char* const vs = smem + (sb - smem) + VRING;
+#pragma unroll
+                for (int i = 0; i < CPS; ++i) {
+                    const int row = i * RPI + lrow;
+                    if (row < nlo) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                }
+            }
             float tmax = fmaxf(S[0], S[1]);
 #pragma unroll
             for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, S[i]), S[i + 1]);

@@ -398,3 +398,49 @@ def test_several_queries_per_sequence(nq, shape):
         Or, Lr = oracle.attention(w, levels=[li], suffix=False)
         check(to_np(Op), to_np(Lp), Or, Lr, f"level {li} nq={nq} {shape}")
     ctx.close()
+
+
+@pytest.mark.parametrize("shape", ["mha", "gqa8", "gqa4_nq3"])
+def test_suffix_ignores_unwritten_cache_rows(shape):
+    """A padded cache: every sequence owns a slot longer than its suffix, and the rows behind the suffix (and the slots
+    of empty sequences) hold NaN, as memory that was never written may.  No such row may reach a result: the kernels
+    read rows outside a sequence's range when they re-read a window or fill a batch, and must neutralise them."""
+    say(f"unwritten cache rows {shape}")
+    rng = np.random.default_rng(7)
+    B = 33
+    ln = rng.integers(0, 60, size=B).astype(np.int32)
+    ln[:8] = [0, 1, 2, 5, 31, 32, 33, 0]
+    if shape == "mha":
+        w = wl.make_workload(shape, 91, B, 4, 4, 128, [(1, 70, B)], 0, 0, lengths=ln)
+    elif shape == "gqa8":
+        w = wl.make_workload(shape, 92, B, 16, 2, 128, [(1, 70, B)], 0, 0, lengths=ln)
+    else:
+        w = wl.make_workload(shape, 93, B, 8, 2, 128, [(1, 70, B)], 0, 0, lengths=ln, nq=3)
+    Ks, Vs, off, cap = wl.with_room(w, 9)
+    owned = np.zeros(Ks.shape[0], dtype=bool)
+    for b in range(B):
+        owned[off[b]: off[b] + ln[b]] = True
+    Ks[~owned] = 0x7FC0     # bf16 NaN
+    Vs[~owned] = 0x7FC0
+    dw = dev.to_device(w)
+    dK, dV, doff = dev.bf16_tensor(Ks, "cuda:0"), dev.bf16_tensor(Vs, "cuda:0"), torch.from_numpy(off).cuda()
+    Oref, Lref = oracle.attention(w)
+    Osuf, Lsuf = oracle.attention(w, levels=[])
+    for kernel in (1, 2):
+        ctx = dev.make_context(dw, parts=16)
+        ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
+        for chunk in (0, 32):
+            ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
+            O, L, intact = outputs(dw, torch.float32)
+            hb.hg_suffix_attn(ctx, dw.Q, dK, dV, doff, dw.lengths, dw.max_len, O, L, dw.scale)
+            assert intact()
+            check(to_np(O), to_np(L), Osuf, Lsuf, f"suffix over a padded cache {shape} kernel={kernel} chunk={chunk}")
+            O, L, intact = outputs(dw, torch.float32)
+            hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dK, dV, doff, dw.lengths, dw.max_len, O, L, dw.scale)
+            assert intact()
+            check(to_np(O), to_np(L), Oref, Lref, f"fused over a padded cache {shape} kernel={kernel} chunk={chunk}")
+            O, L, intact = outputs(dw, torch.float32)
+            hb.hg_naive_attn(ctx, dw.Q, dw.levels, dK, dV, doff, dw.lengths, dw.max_len, O, L, dw.scale)
+            assert intact()
+            check(to_np(O), to_np(L), Oref, Lref, f"naive over a padded cache {shape} kernel={kernel} chunk={chunk}")
+        ctx.close()
