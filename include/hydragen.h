@@ -76,7 +76,7 @@ enum {
     HG_OPT_WIDE_SLOTS = 7,    /* CUs per XCD (1..32) that the persistent 256-row kernel occupies; 0 = automatic */
     HG_OPT_NUM_QUERIES = 8,   /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
     HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10, /* matrix-core suffix kernel: consecutive work items one wavefront takes (1..1024; 0 = automatic) */
-    HG_OPT_SUFFIX_KERNEL = 9  /* suffix kernel: 0 automatic (matrix-core kernel when D = 128, the rows are packed and a KV head serves >= 4 query rows of a sequence; else the vector-ALU kernel), 1 always vector-ALU, 2 matrix-core wherever D = 128 and the rows are packed */
+    HG_OPT_SUFFIX_KERNEL = 9  /* suffix kernel: 0 automatic (matrix-core kernel when D = 128 and a KV head serves >= 4 query rows of a sequence; else the vector-ALU kernel), 1 always vector-ALU, 2 matrix-core wherever D = 128 */
 };
 enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };
 
@@ -186,8 +186,10 @@ typedef struct {
 /*
  * hg_suffix_attn / hg_hydragen_attn with the suffix rows read through a page table: same results as the
  * calls above on the rows that the table designates (lengths: DEVICE int32[B], rows above max_len are ignored).
- * A work item of the suffix kernel covers at most 32 pages, so the workspace must have room for
- * ceil(max_len / (32 * page_size)) partial results (plus one per shared level), else HG_ERR_WORKSPACE.
+ * A work item of the vector-ALU suffix kernel covers at most 32 pages, so when that kernel runs (see
+ * HG_OPT_SUFFIX_KERNEL) the workspace must have room for ceil(max_len / (32 * page_size)) partial results (plus one
+ * per shared level), else HG_ERR_WORKSPACE.  Pool rows that no sequence owns (page tails, free pages) may hold
+ * anything, NaN included.
  */
 int hg_suffix_attn_paged(hg_ctx* ctx, const void* Q, const hg_paged_kv* kv, const int32_t* lengths, int max_len,
                          int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype, float* LSE);

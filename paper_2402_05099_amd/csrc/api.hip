@@ -178,7 +178,9 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
     p.gt = pick_gt(G);
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
-    p.mfma = D == 128 && !paged && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
+    (void)paged;
+    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
+    if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
         if (p.chunk > max_chunk) p.chunk = max_chunk;
@@ -476,7 +478,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
         p.nchunks = ceil_div(max_len, p.chunk);
     }
-    if (p.chunk > max_chunk) return HG_ERR_WORKSPACE;
+    if (!p.mfma && p.chunk > max_chunk) return HG_ERR_WORKSPACE;
     if (p.nchunks == 1)
         return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
                           direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw);
@@ -619,7 +621,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
             return HG_ERR_WORKSPACE;
         }
     }
-    if (has_suffix && sp.chunk > max_chunk) return HG_ERR_WORKSPACE;
+    if (has_suffix && !sp.mfma && sp.chunk > max_chunk) return HG_ERR_WORKSPACE;
     const int np = total_parts();
     hipStream_t s = c->stream;
     if (np == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);

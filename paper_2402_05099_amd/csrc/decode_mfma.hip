@@ -56,8 +56,11 @@ __device__ __forceinline__ void wait_vm() {
 
 }  // namespace
 
-template <int NS>
-__global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
+// PAGED: the suffix rows live in a page pool and are found through a page table (a.pg); rows are then logical rows of
+// the sequence, a stage is 32 aligned logical rows and is never shifted, and the four rows of one copy instruction
+// lie in one page (pages hold a power of two >= 16 rows), so a copy still has one scalar base.
+template <int NS, bool PAGED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
     constexpr int VRING = NS * STB;
     constexpr int QOPS = CPS, KVOPS = 2 * CPS;     // copy instructions per ring element
@@ -74,6 +77,7 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
     const const_i32_ptr lengths_c = (const_i32_ptr)(uintptr_t)a.lengths;
     const const_i32_ptr offsets_c = (const_i32_ptr)(uintptr_t)a.offsets;
+    const const_i32_ptr table_c = (const_i32_ptr)(uintptr_t)a.pg.table;
 
     // One work item: (sequence b, key chunk c, 32-row tile rt, KV head kvh), adjacent items on adjacent KV heads.
     // Everything here is wavefront-uniform.
@@ -104,11 +108,11 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
     // key range of the item whose index fields are set
     auto range_of = [&](Item& it) {
         it.count = __builtin_amdgcn_readfirstlane(max(min(lengths_c[it.b], a.max_len), 0));
-        it.off = __builtin_amdgcn_readfirstlane(offsets_c[it.b]);
+        it.off = PAGED ? 0 : __builtin_amdgcn_readfirstlane(offsets_c[it.b]);
         const int lo = it.c * a.chunk, hi = min(lo + a.chunk, it.count);
         it.ks = __builtin_amdgcn_readfirstlane(it.off + lo);
         it.ke = __builtin_amdgcn_readfirstlane(it.off + max(hi, lo));
-        it.kwin = max(it.ke - KT, 0);
+        it.kwin = PAGED ? 0x3fffffff : max(it.ke - KT, 0);   // paged: stages stay where they are, rows past ke are masked
         it.nst = (it.ke - it.ks + KT - 1) / KT;
     };
 
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
             if (++p_item >= item1) return;
             next_index(pit);
         }
-        const int rowclamp = min(pit.ke - 1 - pit.kwin, KT - 1);   // < 31 only when the range ends before row 32 of the tensor
+        const int rowclamp = PAGED ? KT - 1 : min(pit.ke - 1 - pit.kwin, KT - 1);   // < 31 only when the range ends before row 32 of the tensor
         if (rowclamp != voff_clamp) {
             voff_clamp = rowclamp;
 #pragma unroll
@@ -213,6 +217,27 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
 #pragma unroll
             for (int i = 0; i < CPS; ++i) copy16(qg, voffQ[i], dst + i * (RPI * ROWB));
             pending += QOPS;
+        } else if (PAGED) {
+            // logical rows r0 .. r0+31 of the sequence: copy i takes rows r0 + 4i .. +3, all in one page
+            const int r0 = pit.ks + p_el * KT;
+            const int shift = a.pg.shift, ps_mask = (1 << shift) - 1;
+            const int64_t trow = (int64_t)pit.b * a.pg.stride;
+            const int e0 = min(r0 >> shift, a.pg.stride - 1), e1 = min((r0 + KT / 2) >> shift, a.pg.stride - 1);
+            const int pg0 = min(max(table_c[trow + e0], 0), a.pg.n_pages - 1);   // pages of rows r0.. and r0+16..
+            const int pg1 = min(max(table_c[trow + e1], 0), a.pg.n_pages - 1);
+#pragma unroll
+            for (int i = 0; i < CPS; ++i) {
+                const int jr = r0 + i * RPI;
+                const int page = i < CPS / 2 ? pg0 : pg1;
+                const int64_t prow = ((int64_t)page << shift) + (jr & ps_mask);
+                const int64_t goff = prow * rstride_b + (int64_t)pit.kvh * ROWB;
+                const unsigned char* const kg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Ks) + goff);
+                const unsigned char* const vg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Vs) + goff);
+                const unsigned back = (unsigned)(i * RPI) * rstride_b;    // voffK/V count rows from the stage's first row
+                copy16(kg, voffK[i] - back, dst + i * (RPI * ROWB));
+                copy16(vg, voffV[i] - back, dst + VRING + i * (RPI * ROWB));
+            }
+            pending += KVOPS;
         } else {
             const int k0c = min(pit.ks + p_el * KT, pit.kwin);
             const int64_t goff = (int64_t)k0c * rstride_b + (int64_t)pit.kvh * ROWB;
@@ -359,6 +384,17 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(DecodeArgs a) {
                     if (ri < lo_i || ri >= hi_i) S[i] = -INFINITY;
                 }
             }
+            if (PAGED && key0 + KT > cit.ke) {
+                // the rows past the range are a page's unwritten tail (or another page altogether): clear their V rows
+                // in LDS, since their zero probabilities would still turn a NaN into a NaN in the second product
+                const int nhi = cit.ke - key0;
+                unsigned char* const vs = smem + (sb - smem) + VRING;
+#pragma unroll
+                for (int i = 0; i < CPS; ++i) {
+                    const int row = i * RPI + lrow;
+                    if (row >= nhi) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                }
+            }
             if (k0c != key0) {
                 // The stage rows before its first key were re-read from below the range: they may lie in another
                 // sequence's slot of the cache, possibly padding that was never written.  Their probabilities are
@@ -452,9 +488,14 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
 #endif
     constexpr int NS = HG_DM_NS;
     if (a.items == 0) return hipSuccess;
-    if (a.ipw < 1 || a.n_levels != 0 || a.pg.table != nullptr) return hipErrorInvalidValue;
+    if (a.ipw < 1 || a.n_levels != 0) return hipErrorInvalidValue;
     const int grid = (a.items + a.ipw - 1) / a.ipw;
-    decode_mfma_kernel<NS><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    if (a.pg.table) {
+        if (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1) return hipErrorInvalidValue;
+        decode_mfma_kernel<NS, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    } else {
+        decode_mfma_kernel<NS, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    }
     return hipGetLastError();
 }
 

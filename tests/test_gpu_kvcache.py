@@ -34,6 +34,7 @@ def test_paged_suffix_attn(idx, page_size):
     pg = wl.make_paged(w, page_size)
     kv = dev.paged_to_device(pg)
     ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, 1)
     Oref, Lref = oracle.attention(w, levels=[])
     O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
     L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
@@ -41,11 +42,53 @@ def test_paged_suffix_attn(idx, page_size):
     torch.cuda.synchronize()
     check(to_np(O), to_np(L), Oref, Lref, f"paged suffix idx={idx} ps={page_size}")
     # the packed cache holds the same rows and the same (vector-ALU) kernel walks them in the same order: identical bits
-    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, 1)
     O2, L2 = torch.empty_like(O), torch.empty_like(L)
     hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O2, L2, dw.scale)
     torch.cuda.synchronize()
     assert torch.equal(O, O2) and torch.equal(L, L2)
+    ctx.close()
+
+
+@pytest.mark.parametrize("kernel", [1, 2], ids=["valu", "mfma"])
+@pytest.mark.parametrize("page_size", [16, 32, 128])
+@pytest.mark.parametrize("shape", ["mha", "gqa8", "gqa4_nq3"])
+def test_paged_suffix_both_kernels_and_unwritten_rows(shape, page_size, kernel):
+    """Both suffix kernels through the page table; the pool rows that no sequence owns (page tails, free pages) hold
+    NaN, as memory that was never written may, and must not reach a result."""
+    say(f"paged {shape} page_size={page_size} kernel={kernel}")
+    rng = np.random.default_rng(11)
+    B = 27
+    ln = rng.integers(0, 330, size=B).astype(np.int32)
+    ln[:8] = [0, 1, 15, 16, 17, 31, 32, 33]
+    if shape == "mha":
+        w = wl.make_workload(shape, 94, B, 4, 4, 128, [(1, 60, B)], 0, 0, lengths=ln)
+    elif shape == "gqa8":
+        w = wl.make_workload(shape, 95, B, 16, 2, 128, [(1, 60, B)], 0, 0, lengths=ln)
+    else:
+        w = wl.make_workload(shape, 96, B, 8, 2, 128, [(1, 60, B)], 0, 0, lengths=ln, nq=3)
+    pg = wl.make_paged(w, page_size)
+    owned = np.zeros(pg.K.shape[0], dtype=bool)
+    for b in range(B):
+        j = np.arange(int(ln[b]))
+        owned[pg.table[b, j // page_size].astype(np.int64) * page_size + j % page_size] = True
+    pg.K[~owned] = 0x7FC0     # bf16 NaN
+    pg.V[~owned] = 0x7FC0
+    dw = dev.to_device(w)
+    kv = dev.paged_to_device(pg)
+    ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
+    Osuf, Lsuf = oracle.attention(w, levels=[])
+    Oref, Lref = oracle.attention(w)
+    for chunk in (0, 64):
+        ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
+        O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
+        L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+        hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), Osuf, Lsuf, f"paged suffix {shape} ps={page_size} kernel={kernel} chunk={chunk}")
+        O, L = dev.hydragen_paged(ctx, dw, kv, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), Oref, Lref, f"paged fused {shape} ps={page_size} kernel={kernel} chunk={chunk}")
     ctx.close()
 
 
