@@ -31,6 +31,7 @@ EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
+    "hg_debug_wide_plan", "hg_debug_suffix_plan",
 )
 
 
@@ -98,6 +99,10 @@ def lib() -> ctypes.CDLL:
         L.hg_kv_append.restype = ci
         L.hg_kv_append_paged.argtypes = [vp, vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci]
         L.hg_kv_append_paged.restype = ci
+        L.hg_debug_wide_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
+        L.hg_debug_wide_plan.restype = ci
+        L.hg_debug_suffix_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
+        L.hg_debug_suffix_plan.restype = ci
         L.hg_read_stage_timings.argtypes = [vp, ctypes.POINTER(cf), ci]
         L.hg_read_stage_timings.restype = ci
         L.hg_strerror.argtypes = [ci]
@@ -372,3 +377,19 @@ def hg_kv_append_paged(ctx: Context, Knew, Vnew, kv: PagedKV, lengths, capacity:
     st = kv.c_struct()
     _check(lib().hg_kv_append_paged(ctx.h, _p(Knew), _p(Vnew), ctypes.byref(st), _p(lengths), capacity, B, Hkv, D),
            "hg_kv_append_paged")
+
+
+def hg_debug_wide_plan(n_blocks: int, max_rows: int, max_seqs: int, Hkv: int, rows_per_seq: int, max_parts: int, slots_per_xcd: int):
+    """dict of the persistent shared-block kernel's work partition, or None if the level does not fit (host only)."""
+    out = (ctypes.c_int * 8)()
+    if not lib().hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, out):
+        return None
+    return dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts"), list(out)))
+
+
+def hg_debug_suffix_plan(B: int, nq: int, Hq: int, Hkv: int, D: int, max_len: int, page_size: int = 0):
+    """dict of the suffix kernel choice and chunking with default options, or None on invalid arguments (host only)."""
+    out = (ctypes.c_int * 4)()
+    if not lib().hg_debug_suffix_plan(B, nq, Hq, Hkv, D, max_len, page_size, out):
+        return None
+    return dict(zip(("chunk", "nchunks", "mfma", "gt"), list(out)))

@@ -822,6 +822,29 @@ int hg_read_stage_timings(hg_ctx* c, float* ms, int n_calls) {
     return n;
 }
 
+int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts, int slots_per_xcd,
+                       int out[8]) {
+    if (!out || n_blocks < 1 || max_rows < 0 || max_seqs < 0 || Hkv < 1 || rows_per_seq < 1) return 0;
+    hg::LevelDev lv{};
+    lv.n_blocks = n_blocks;
+    lv.max_rows = max_rows;
+    lv.max_seqs = max_seqs;
+    hg::WidePlan p{};
+    if (!hg::plan_prefix_wide(lv, Hkv, rows_per_seq, max_parts, slots_per_xcd, &p)) return 0;
+    out[0] = p.n_c; out[1] = p.ncols; out[2] = p.rowgroups; out[3] = p.T;
+    out[4] = p.slots; out[5] = p.tpx; out[6] = p.quota; out[7] = p.nparts;
+    return 1;
+}
+
+int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int page_size, int out[4]) {
+    if (!out || B < 1 || nq < 1 || Hkv < 1 || Hq < Hkv || Hq % Hkv != 0 || (D != 64 && D != 128) || max_len < 0 || page_size < 0) return 0;
+    hg_ctx c{};   // default options
+    c.opt_nq = nq;
+    const SuffixPlan p = plan_suffix(&c, max_len, Hq / Hkv, B, nq, Hkv, D, page_size > 0, page_size > 0 ? 32 * page_size : 1 << 30);
+    out[0] = p.chunk; out[1] = p.nchunks; out[2] = p.mfma ? 1 : 0; out[3] = p.gt;
+    return 1;
+}
+
 const char* hg_strerror(int code) {
     switch (code) {
         case HG_OK: return "ok";

@@ -401,11 +401,16 @@ bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slo
     if (max_parts < 1) return false;
     int np = parts_needed(q);
     if (np > max_parts) {
-        // longer ranges per team (some teams then stay idle) until the parts fit; a range of one whole column
-        // always fits in one part
-        q = max_parts >= 2 ? (p.n_c + max_parts - 2) / (max_parts - 1) : p.n_c;
-        np = parts_needed(q);
-        if (np > max_parts) { q = p.n_c; np = 1; }
+        // Longer ranges per team (some teams then stay idle) until the parts fit, as long as the teams still cover
+        // the whole space; otherwise whole columns per team, which always fits in one part.
+        const long long qa = max_parts >= 2 ? (p.n_c + max_parts - 2) / (max_parts - 1) : 0;
+        if (qa >= 1 && qa * nteams >= total && parts_needed(qa) <= max_parts) {
+            q = qa;
+            np = parts_needed(qa);
+        } else {
+            q = (ncols + nteams - 1) / nteams * p.n_c;
+            np = 1;
+        }
     }
     if (q >= (1LL << 30)) return false;
     p.quota = (int)q;

@@ -444,3 +444,21 @@ def test_suffix_ignores_unwritten_cache_rows(shape):
             assert intact()
             check(to_np(O), to_np(L), Oref, Lref, f"naive over a padded cache {shape} kernel={kernel} chunk={chunk}")
         ctx.close()
+
+
+def test_persistent_kernel_more_columns_than_teams_and_one_part():
+    """320 (block, KV head) columns against 256 teams with room for a single partial result: every team must take
+    whole columns, and all of them (a plan that gave each team one column dropped the rest)."""
+    say("many columns, one part")
+    w = wl.make_workload("many_columns", 97, 1600, 32, 8, 128, [(40, 45, 40)], 0, 0, lengths=np.zeros(1600, np.int32))
+    dw = dev.to_device(w)
+    plan = hb.hg_debug_wide_plan(40, 45, 40, 8, 4, 1, 32)
+    assert plan["ncols"] == 320 > 8 * plan["tpx"] and plan["nparts"] == 1 and plan["quota"] == 2 * plan["n_c"]
+    ctx = hb.Context(0, 0)                       # no workspace: the level must run with one part, written directly
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, 2)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    O, L, intact = outputs(dw, torch.float32)
+    hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[0], O, L, dw.scale)
+    assert intact()
+    check(to_np(O), to_np(L), Oref, Lref, "many columns, one part")
+    ctx.close()

@@ -1,0 +1,93 @@
+"""Host logic of the library, checked without a GPU: the work partition of the persistent shared-block kernel must
+cover every (column, stage) position exactly once within the partial results it promises, for any level shape, CU
+count and workspace; the suffix planner must respect its limits.  The walk below is the kernel's own rule (team t owns
+flattened positions [t*quota, (t+1)*quota); part index = team - floor(column * n_c / quota)), restated in Python."""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2402_05099_amd import binding as hb
+
+
+def walk(plan):
+    """pieces[(column)] = list of (first stage, stages, part index, team) in the order the teams produce them"""
+    n_c, ncols, quota = plan["n_c"], plan["ncols"], plan["quota"]
+    total = ncols * n_c
+    pieces = {}
+    for team in range(8 * plan["tpx"]):
+        f0, f1 = team * quota, min((team + 1) * quota, total)
+        c, k0 = divmod(f0, n_c) if f0 < f1 else (0, 0)
+        while f0 < f1:
+            ln = min(n_c - k0, f1 - f0)
+            sp = team - (c * n_c) // quota
+            pieces.setdefault(c, []).append((k0, ln, sp, team))
+            f0 += ln
+            c += 1
+            k0 = 0
+    return pieces
+
+
+SHAPES = [
+    # n_blocks, max_rows, max_seqs, Hkv, rows_per_seq
+    (1, 16384, 1024, 40, 1), (1, 4096, 512, 8, 8), (1, 2048, 256, 40, 1), (16, 512, 128, 40, 1), (1, 1024, 2048, 40, 1),
+    (1, 16384, 1024, 1, 8), (3, 77, 300, 2, 4), (1, 1, 129, 1, 1), (1, 33, 257, 3, 1), (5, 1000, 9000, 4, 2), (1, 31, 40000, 1, 1),
+    (2, 100000, 130, 8, 1), (7, 65, 200, 5, 6),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("slots", [1, 3, 4, 12, 20, 32])
+@pytest.mark.parametrize("max_parts", [1, 2, 3, 24, 64])
+def test_wide_plan_covers_every_stage_once(shape, slots, max_parts):
+    n_blocks, max_rows, max_seqs, Hkv, rps = shape
+    plan = hb.hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rps, max_parts, slots)
+    assert plan is not None, "one part per row always fits"
+    rows = max_seqs * rps
+    mtiles = -(-rows // 256)
+    assert plan["n_c"] == -(-max_rows // 32)
+    assert plan["rowgroups"] * plan["T"] >= mtiles and (plan["rowgroups"] - 1) * plan["T"] < mtiles
+    assert plan["T"] <= plan["slots"] == slots and plan["tpx"] == slots // plan["T"] >= 1
+    assert plan["ncols"] == n_blocks * Hkv * plan["rowgroups"]
+    assert 1 <= plan["nparts"] <= max_parts
+    pieces = walk(plan)
+    assert sorted(pieces) == list(range(plan["ncols"])), "every column is visited"
+    for c, ps in pieces.items():
+        ps.sort()
+        assert ps[0][0] == 0 and sum(p[1] for p in ps) == plan["n_c"], "the pieces of a column tile its stages"
+        for (k0, ln, _, _), (k1, _, _, _) in zip(ps, ps[1:]):
+            assert k0 + ln == k1
+        assert [p[2] for p in ps] == list(range(len(ps))), "part indices count the pieces of the column from 0"
+        assert len(ps) <= plan["nparts"]
+    # the teams that exist can take the whole space
+    assert 8 * plan["tpx"] * plan["quota"] >= plan["ncols"] * plan["n_c"]
+
+
+def test_wide_plan_rejects_what_it_cannot_run():
+    assert hb.hg_debug_wide_plan(1, 0, 100, 1, 1, 4, 32) is None      # no keys
+    assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 0, 32) is None     # no room for a result
+    assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 4, 33) is None     # more CUs per XCD than there are
+    assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 4, 0) is None
+
+
+@pytest.mark.parametrize("B,nq,Hq,Hkv,D,max_len,ps", [
+    (1024, 1, 40, 40, 128, 128, 0), (512, 1, 64, 8, 128, 512, 0), (512, 1, 64, 8, 128, 512, 16), (4, 1, 4, 4, 64, 16, 0),
+    (1024, 4, 40, 40, 128, 128, 0), (2048, 1, 40, 40, 128, 64, 0), (3, 1, 8, 1, 128, 5000, 0), (256, 1, 40, 40, 128, 4096, 16),
+    (1, 1, 1, 1, 64, 1, 0), (7, 6, 8, 2, 64, 300, 32),
+])
+def test_suffix_plan_limits(B, nq, Hq, Hkv, D, max_len, ps):
+    p = hb.hg_debug_suffix_plan(B, nq, Hq, Hkv, D, max_len, ps)
+    assert p is not None
+    assert p["chunk"] % 32 == 0 and p["chunk"] >= 32
+    assert p["nchunks"] * p["chunk"] >= max_len and (p["nchunks"] - 1) * p["chunk"] < max(max_len, 1)
+    G = Hq // Hkv
+    assert p["mfma"] == int(D == 128 and nq * G >= 4), "matrix cores when a KV head serves four or more rows of a sequence"
+    assert G % p["gt"] == 0 and p["gt"] in (1, 2, 4, 8)
+    if ps and not p["mfma"]:
+        assert p["chunk"] <= 32 * ps, "a vector-ALU work item covers at most 32 pages"
+
+
+def test_suffix_plan_rejects_bad_arguments():
+    assert hb.hg_debug_suffix_plan(4, 1, 6, 4, 128, 10) is None     # Hq not a multiple of Hkv
+    assert hb.hg_debug_suffix_plan(4, 1, 4, 4, 96, 10) is None      # unsupported head dimension
+    assert hb.hg_debug_suffix_plan(0, 1, 4, 4, 128, 10) is None
