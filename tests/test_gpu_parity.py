@@ -462,3 +462,28 @@ def test_persistent_kernel_more_columns_than_teams_and_one_part():
     assert intact()
     check(to_np(O), to_np(L), Oref, Lref, "many columns, one part")
     ctx.close()
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_fused_call_at_every_workspace_size(idx):
+    """The planner trades partial results for parallelism: from the smallest workspace the call accepts (one part per
+    level and one for the suffix) upwards, every size must give the same attention."""
+    say(f"workspace sweep idx={idx}")
+    w, dw = workload(idx)
+    Oref, Lref = oracle.attention(w)
+    need = len(w.levels) + 1
+    for parts in list(range(need, need + 6)) + [12, 64]:
+        for kernel in (1, 2):
+            ctx = dev.make_context(dw, parts=parts)
+            ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
+            ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, 32)     # many suffix chunks wanted: the planner has to give way
+            O, L, intact = outputs(dw, torch.float32)
+            hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+            assert intact()
+            check(to_np(O), to_np(L), Oref, Lref, f"fused idx={idx} parts={parts} kernel={kernel}")
+            ctx.close()
+    small = dev.make_context(dw, parts=need - 1)
+    with pytest.raises(hb.HydragenError) as e:
+        dev.hydragen(small, dw, torch.float32)
+    assert e.value.code == hb.HG_ERR_WORKSPACE
+    small.close()
