@@ -6,36 +6,60 @@ namespace hg {
 
 // D/4 lanes per query row, 4 output elements per lane.  Parts with LSE = -inf are skipped (their O may
 // be uninitialised memory); a row whose parts are all empty becomes O = 0, LSE = -inf.
+// Parts are taken four at a time: their LSEs, then the O pieces of the non-empty ones, are loaded before any is
+// used, so that a lane has up to four 16-byte loads in flight; the running maximum is carried across groups (the
+// accumulators are rescaled when it grows), which equals the one-pass formula with the global maximum.
 template <int D, bool IN_BF16, bool OUT_BF16>
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     constexpr int LPR = D / 4;
     constexpr int RPB = 256 / LPR;
+    constexpr int U = 4;
     const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / LPR;
     if (row >= a.rows) return;
     const int c = threadIdx.x % LPR;
 
-    float m = -INFINITY;
-    for (int i = 0; i < a.n; ++i) m = fmaxf(m, a.L[i][row]);
-
+    float m = -INFINITY;            // running maximum of the LSEs seen so far
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
-    if (m > -INFINITY) {
-        for (int i = 0; i < a.n; ++i) {
-            const float li = a.L[i][row];
-            if (li == -INFINITY) continue;
-            const float w = __builtin_amdgcn_exp2f((li - m) * kLog2e);
-            den += w;
-            float o[4];
-            if constexpr (IN_BF16) {
-                const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.O[i]) + row * D + 4 * c);
-                o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
-            } else {
-                const float4 v = *reinterpret_cast<const float4*>(static_cast<const float*>(a.O[i]) + row * D + 4 * c);
-                o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-            }
+    for (int i0 = 0; i0 < a.n; i0 += U) {
+        float li[U];
+        float o[U][4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = fmaf(w, o[j], acc[j]);
+        for (int u = 0; u < U; ++u) li[u] = i0 + u < a.n ? a.L[i0 + u][row] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            o[u][0] = o[u][1] = o[u][2] = o[u][3] = 0.f;
+            if (li[u] != -INFINITY) {
+                if constexpr (IN_BF16) {
+                    const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.O[i0 + u]) + row * D + 4 * c);
+                    o[u][0] = bf16_lo(v.x); o[u][1] = bf16_hi(v.x); o[u][2] = bf16_lo(v.y); o[u][3] = bf16_hi(v.y);
+                } else {
+                    const float4 v = *reinterpret_cast<const float4*>(static_cast<const float*>(a.O[i0 + u]) + row * D + 4 * c);
+                    o[u][0] = v.x; o[u][1] = v.y; o[u][2] = v.z; o[u][3] = v.w;
+                }
+            }
         }
+        float gm = li[0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) gm = fmaxf(gm, li[u]);
+        if (gm > m) {               // (false while everything seen is empty)
+            const float r = __builtin_amdgcn_exp2f((m - gm) * kLog2e);   // m = -inf: 0, and acc = den = 0 anyway
+            den *= r;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] *= r;
+            m = gm;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (li[u] != -INFINITY) {
+                const float w = __builtin_amdgcn_exp2f((li[u] - m) * kLog2e);
+                den += w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = fmaf(w, o[u][j], acc[j]);
+            }
+        }
+    }
+    if (m > -INFINITY) {
         const float inv = 1.0f / den;
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] *= inv;
