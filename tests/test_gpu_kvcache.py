@@ -163,13 +163,14 @@ def test_kv_append_packed_and_paged(nq):
     ctx.close()
 
 
+@pytest.mark.parametrize("idx", [5, 4], ids=["tree_mha", "gqa"])
 @pytest.mark.parametrize("paged", [False, True])
-def test_decode_steps_append_then_attend_in_a_graph(paged):
+def test_decode_steps_append_then_attend_in_a_graph(paged, idx):
     """One decode step = cache update + fused attention, captured once and replayed: lengths advance on the device,
     the launch sequence never changes (Sec. 3.5), and every step matches the oracle on the grown cache."""
-    say(f"decode steps paged={paged}")
+    say(f"decode steps paged={paged} idx={idx}")
     steps = 4
-    w = wl.scaled_down(5)
+    w = wl.scaled_down(idx)
     dw = dev.to_device(w)
     s = torch.cuda.Stream()
     ctx = hb.Context(0, hb.hg_workspace_bytes(dw.B, dw.Hq, dw.D, 24), stream=s)
