@@ -202,7 +202,7 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
 
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
                const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
-               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0) {
+               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0, bool seg = false) {
     DecodeArgs a{};
     a.pg = pg;
     a.Q = static_cast<const uint16_t*>(Q);
@@ -221,6 +221,7 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
     a.scale = scale;
     a.out = out;
     if (mfma) {
+        a.seg = seg ? 1 : 0;
         const int64_t items = (int64_t)B * nchunks * ceil_div(nq * a.G, 32) * Hkv;
         if (items >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
         a.items = (int)items;
@@ -582,6 +583,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     int ns[HG_MAX_LEVELS];
     int nlev = 0;
     int wide_slots = 32;
+    bool tiny = false;   // so little work that the event edges between two streams cost more than overlap can gain
     if (has_suffix && c->opt_overlap != 1) {
         double flops = 0.0;
         int T = 1;
@@ -593,6 +595,8 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         }
         const double bytes = 4.0 * B * nq * (0.75 * max_len) * Hkv * D;   // K and V, bf16; mean length taken as 0.75 max_len
         wide_slots = pick_wide_slots(flops, bytes, T);
+        tiny = c->opt_overlap == 0 && flops / 1.14e15 + bytes / 6.0e12 < 60e-6;
+        if (tiny) wide_slots = 32;
     }
     for (int i = 0; i < n_levels; ++i) {
         LevelDev d = to_dev(levels[i], B);
@@ -637,10 +641,11 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     }
 
     // Two streams unless asked for one.  In automatic mode a call whose levels all run in the persistent kernel on
-    // the whole chip stays on one stream: there is no CU left for the suffix kernel to run beside it.
+    // the whole chip stays on one stream (there is no CU left for the suffix kernel to run beside it), and so does a
+    // call with less than about 60 us of work (forking and joining streams costs more than it can gain).
     bool all_wide_full = nlev > 0;
     for (int i = 0; i < nlev; ++i) all_wide_full = all_wide_full && plan[i].wide && plan[i].wp.slots == 32;
-    const bool overlap = c->opt_overlap != 1 && has_suffix && nlev > 0 && !(c->opt_overlap == 0 && all_wide_full);
+    const bool overlap = c->opt_overlap != 1 && has_suffix && nlev > 0 && !(c->opt_overlap == 0 && (all_wide_full || tiny));
     hipStream_t ssfx = s;
     if (overlap) {
         if (hipEventRecord(c->ev_fork, s) != hipSuccess) return HG_ERR_HIP;
@@ -788,6 +793,36 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (parts.cap < 1) return HG_ERR_WORKSPACE;
     if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
     if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
+    if (D == 128 && nq * G >= 4 && c->opt_suffix_kernel != 1) {
+        // Several query rows per KV head: the per-sequence kernel on the matrix cores, once per level (every sequence
+        // walks the block that covers it by itself) and once for the suffix, each writing its own partial results.
+        int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 1024;
+        const int cap = parts.cap < HG_MAX_PARTS ? parts.cap : HG_MAX_PARTS;
+        auto parts_for = [&](int ch) {
+            int n = has_suffix ? ceil_div(max_len, ch) : 0;
+            for (int i = 0; i < n_levels; ++i) if (lv[i].max_rows > 0) n += ceil_div(lv[i].max_rows, ch);
+            return n;
+        };
+        while (parts_for(chunk) > cap && chunk < (1 << 29)) chunk *= 2;
+        if (parts_for(chunk) > cap) return HG_ERR_WORKSPACE;
+        int first = 0;
+        for (int i = 0; i < n_levels; ++i) {
+            if (lv[i].max_rows <= 0) continue;
+            const int n = ceil_div(lv[i].max_rows, chunk);
+            rc = run_decode(Q, 1, &lv[i], lv[i].K, lv[i].V, nullptr, nullptr, lv[i].max_rows, B, nq, Hq, Hkv, D, scale, chunk, n, 1,
+                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, true);
+            if (rc) return rc;
+            first += n;
+        }
+        if (has_suffix) {
+            const int n = ceil_div(max_len, chunk);
+            rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, chunk, n, 1,
+                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, false);
+            if (rc) return rc;
+            first += n;
+        }
+        return run_merge(first, parts, 0, D, O_out, o_dtype, LSE_out, s);
+    }
     int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 512;
     int nchunks = ceil_div((int)nmax, chunk);
     const int cap = parts.cap < 32 ? parts.cap : 32;

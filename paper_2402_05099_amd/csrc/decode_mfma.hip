@@ -59,7 +59,9 @@ __device__ __forceinline__ void wait_vm() {
 // PAGED: the suffix rows live in a page pool and are found through a page table (a.pg); rows are then logical rows of
 // the sequence, a stage is 32 aligned logical rows and is never shifted, and the four rows of one copy instruction
 // lie in one page (pages hold a power of two >= 16 rows), so a copy still has one scalar base.
-template <int NS, bool PAGED>
+// SEG: the key range of sequence b is the block of level a.lv[0] that covers b (the non-decomposed comparison walks
+// the shared blocks per sequence); every query of the sequence sees all of it.
+template <int NS, bool PAGED, bool SEG>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
     constexpr int VRING = NS * STB;
@@ -78,6 +80,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     const const_i32_ptr lengths_c = (const_i32_ptr)(uintptr_t)a.lengths;
     const const_i32_ptr offsets_c = (const_i32_ptr)(uintptr_t)a.offsets;
     const const_i32_ptr table_c = (const_i32_ptr)(uintptr_t)a.pg.table;
+    const const_i32_ptr seq_off_c = (const_i32_ptr)(uintptr_t)a.lv[0].seq_off;
+    const const_i32_ptr kv_off_c = (const_i32_ptr)(uintptr_t)a.lv[0].kv_off;
 
     // One work item: (sequence b, key chunk c, 32-row tile rt, KV head kvh), adjacent items on adjacent KV heads.
     // Everything here is wavefront-uniform.
@@ -107,8 +111,28 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     };
     // key range of the item whose index fields are set
     auto range_of = [&](Item& it) {
-        it.count = __builtin_amdgcn_readfirstlane(max(min(lengths_c[it.b], a.max_len), 0));
-        it.off = PAGED ? 0 : __builtin_amdgcn_readfirstlane(offsets_c[it.b]);
+        if (SEG) {
+            // rows [begin, begin + count) of the block that covers sequence b: the g with seq_off[g] <= b < seq_off[g+1]
+            int begin = 0, count = a.lv[0].max_rows;
+            if (seq_off_c != nullptr) {
+                int lo = 0, hi = a.lv[0].n_blocks;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (seq_off_c[mid + 1] <= it.b) lo = mid + 1;
+                    else hi = mid;
+                }
+                count = 0;
+                if (lo < a.lv[0].n_blocks && seq_off_c[lo] <= it.b) {
+                    begin = kv_off_c[lo];
+                    count = max(min(kv_off_c[lo + 1] - begin, a.lv[0].max_rows), 0);
+                }
+            }
+            it.count = __builtin_amdgcn_readfirstlane(count);
+            it.off = __builtin_amdgcn_readfirstlane(begin);
+        } else {
+            it.count = __builtin_amdgcn_readfirstlane(max(min(lengths_c[it.b], a.max_len), 0));
+            it.off = PAGED ? 0 : __builtin_amdgcn_readfirstlane(offsets_c[it.b]);
+        }
         const int lo = it.c * a.chunk, hi = min(lo + a.chunk, it.count);
         it.ks = __builtin_amdgcn_readfirstlane(it.off + lo);
         it.ke = __builtin_amdgcn_readfirstlane(it.off + max(hi, lo));
@@ -306,8 +330,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             lane_g = rr % a.G;
         }
         qidx = ((int64_t)it.b * a.nq + lane_tq) * a.Hq + it.kvh * a.G + lane_g;
-        vis_end = it.off + it.count - (a.nq - 1 - lane_tq);   // this lane's query sees absolute rows below vis_end
-        causal_from = it.off + it.count - (a.nq - 1);         // below this row every query sees every key
+        vis_end = it.off + it.count - (SEG ? 0 : a.nq - 1 - lane_tq);   // this lane's query sees absolute rows below vis_end
+        causal_from = it.off + it.count - (SEG ? 0 : a.nq - 1);         // below this row every query sees every key
     };
     // position the consumer on the next item that has keys; items without keys get the empty part on the way
     auto c_load = [&](bool first) {
@@ -488,13 +512,15 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
 #endif
     constexpr int NS = HG_DM_NS;
     if (a.items == 0) return hipSuccess;
-    if (a.ipw < 1 || a.n_levels != 0) return hipErrorInvalidValue;
+    if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
     const int grid = (a.items + a.ipw - 1) / a.ipw;
     if (a.pg.table) {
         if (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1) return hipErrorInvalidValue;
-        decode_mfma_kernel<NS, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        decode_mfma_kernel<NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    } else if (a.seg) {
+        decode_mfma_kernel<NS, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else {
-        decode_mfma_kernel<NS, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        decode_mfma_kernel<NS, false, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     }
     return hipGetLastError();
 }

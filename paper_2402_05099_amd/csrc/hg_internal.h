@@ -84,6 +84,8 @@ struct DecodeArgs {
     int64_t units;    // B * nq * nchunks * Hkv * (G / GT)
     int items;        // matrix-core kernel: B * nchunks * ceil(nq*G / 32) * Hkv work items
     int ipw;          // matrix-core kernel: consecutive work items per wavefront
+    int seg;          // matrix-core kernel: 1 = the keys of sequence b are the rows of the block of lv[0] that covers b
+                      // (Ks/Vs then point at that level's tensors; offsets/lengths are unused, no causal bound)
     float scale;
     OutDev out;       // part index = chunk
 };
