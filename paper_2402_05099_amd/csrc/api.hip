@@ -793,7 +793,7 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (parts.cap < 1) return HG_ERR_WORKSPACE;
     if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
     if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
-    if (D == 128 && nq * G >= 4 && c->opt_suffix_kernel != 1) {
+    if (D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || nq * G >= 4)) {
         // Several query rows per KV head: the per-sequence kernel on the matrix cores, once per level (every sequence
         // walks the block that covers it by itself) and once for the suffix, each writing its own partial results.
         int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 1024;
