@@ -54,6 +54,7 @@ def main() -> int:
     ap.add_argument("--paged", type=int, default=0, help="rows per page: the suffix cache is a page pool read through a page table (0 = packed rows, the default)")
     ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
     ap.add_argument("--suffix-kernel", type=int, default=0, help="HG_OPT_SUFFIX_KERNEL: 0 automatic, 1 vector-ALU, 2 matrix-core")
+    ap.add_argument("--graph", action="store_true", help="also time the fused call replayed from a captured HIP graph (reported as graph_ms_per_step; the headline stays the eager call)")
     ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
     args = ap.parse_args()
 
@@ -131,6 +132,27 @@ def main() -> int:
 
     # the timed region: the library's default configuration (suffix and shared-block kernels overlap on two streams)
     ms_per_step, st_timed = timed(args.steps)
+    graph_ms = None
+    if args.graph:
+        # the same call captured once in a HIP graph on a side stream and replayed: no per-launch host work
+        gs = torch.cuda.Stream()
+        ctx.set_stream(gs)
+        with torch.cuda.stream(gs):
+            step()
+        gs.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=gs):
+            step()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ctx.set_stream(None)
     # per-kernel durations for the rooflines: the same K steps again with the kernels serialised on one stream, so
     # that each duration is that kernel alone (when they overlap, each one's events also span the other's work)
     serial_ms_per_step = None
@@ -270,6 +292,7 @@ def main() -> int:
         "naive": None if naive_ms is None else {"ms_per_step": naive_ms, "queries_per_s": B / (naive_ms * 1e-3),
                                                  "speedup_hydragen_over_naive": naive_ms / ms_per_step},
         "kv_append_ms": append_ms,
+        "graph_ms_per_step": graph_ms,
         "parity": parity,
     }
     print(json.dumps(out))
