@@ -361,7 +361,7 @@ def test_planted_key_dominates():
         assert np.abs(O[b] - v).max() < 1e-2
 
 
-# ---- several queries per sequence (App. B's num_queries > 1; causal reading of the design doc) ------------------------
+# ---- several queries per sequence (App. B's num_queries > 1; the causal reading among the new tokens is this build's) ------------------------
 
 def _nq_workload():
     lengths = np.array([0, 1, 2, 3, 4, 9, 5], dtype=np.int32)   # some shorter than nq, one empty
