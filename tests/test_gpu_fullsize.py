@@ -1,5 +1,5 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (default options, bf16 output,
-24 workspace parts): the five configurations, with the oracle evaluated on sampled sequences (first, last,
+24 workspace parts): the five configurations and the paper's microbenchmark shape, with the oracle evaluated on sampled sequences (first, last,
 shortest and longest suffix, block boundaries of the tree) and whole-output properties checked at full size."""
 import sys
 
@@ -56,7 +56,7 @@ def run_and_check(w, dw, what, with_naive=True):
     ctx.close()
 
 
-@pytest.mark.parametrize("idx", [2, 4])
+@pytest.mark.parametrize("idx", [2, 4, 6])
 def test_full_config(idx):
     say(f"full config {idx}")
     w = wl.config(idx)
