@@ -30,6 +30,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 MEASURED_TRAFFIC = {
     ("prefix_level0", "c3_long_P16384"): int((173540.0 / 0.50002 + 51880.4) * 1024),
     ("suffix", "c3_long_P16384"): int((834136.4 / 0.50002 + 20804.8) * 1024),
+    ("prefix_level0", "c4_gqa"): int((12480.9 / 0.50003 + 35728.4) * 1024),
+    ("suffix", "c4_gqa"): int((276987.8 / 0.50003 + 16513.9) * 1024),
 }
 
 
