@@ -205,9 +205,6 @@ __device__ __forceinline__ void wide_piece(const PrefixArgs& a, unsigned char* s
     const float c2 = a.scale * kLog2e;
     const float tau_raw = TAU / c2;
 
-    const int nst = (ke - ks + KT - 1) / KT;       // stages with at least one key
-    const int nfull = (ke - ks) / KT;              // stages with all keys in range
-
     auto mask_stage = [&](floatx16& S, int tstage) {
         const int key0 = ks + tstage * KT;
         const int k0c = min(key0, kwin);
@@ -241,6 +238,23 @@ __device__ __forceinline__ void wide_piece(const PrefixArgs& a, unsigned char* s
     __builtin_amdgcn_s_waitcnt(0x0F70 | (kPrologueOutstanding & 15) | ((kPrologueOutstanding >> 4) << 14));
     __builtin_amdgcn_s_barrier();
 
+    constexpr int kStepOutstanding = INFLIGHT * 2;
+    constexpr int kStepWait = 0x0F70 | (kStepOutstanding & 15) | ((kStepOutstanding >> 4) << 14);
+    const int nst = (ke - ks + KT - 1) / KT;       // stages with at least one key
+    const int nfull = (ke - ks) / KT;              // stages with all keys in range
+
+    if (row0 + w * 32 >= nrows) {
+        // A wavefront whose 32 rows all lie past the block's last row (blocks of <= 224 rows) has nothing to multiply:
+        // it keeps its share of the copies and meets the others at every barrier, one per stage as in step() below.
+        for (int j = 0; j < nst; ++j) {
+            __builtin_amdgcn_s_waitcnt(kStepWait);
+            __builtin_amdgcn_s_barrier();
+            issue_stage(j + NS - 1, (j + NS - 1) & (NS - 1));
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        return;
+    }
+
     uintx4 kf[KS / 2];
     shortx8 vf[DB];
     floatx16 SA, SB;
@@ -263,9 +277,6 @@ __device__ __forceinline__ void wide_piece(const PrefixArgs& a, unsigned char* s
     for (int q = 0; q < KS / 2; ++q) kf[q] = lds_k(1, q);
 #pragma unroll
     for (int db = 0; db < DB; ++db) vf[db] = lds_v(0, 0, db);
-
-    constexpr int kStepOutstanding = INFLIGHT * 2;
-    constexpr int kStepWait = 0x0F70 | (kStepOutstanding & 15) | ((kStepOutstanding >> 4) << 14);
 
     // One pipeline step.  On entry: Scur = scores of stage j, kf = K fragments 0..3 of stage j+1, vf = V fragments
     // of keys 0..15 of stage j.  On exit the same with j+1, Snext = scores of stage j+1.  The copy of stage j+NS-1
