@@ -215,6 +215,29 @@ int hg_kv_append_paged(hg_ctx* ctx, const void* Knew, const void* Vnew, const hg
                        int32_t* lengths, int capacity, int B, int Hkv, int D);
 
 /*
+ * 8-bit suffix cache (not in the paper: a bandwidth variant of the suffix part of Sec. 3.2, the part of the method
+ * that is bound by the bytes it reads).  Ks8, Vs8: one byte per element, [T, Hkv, D], OCP 8-bit floating point E4M3
+ * codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, largest value 448); a key is
+ * code * k_scale and a value code * v_scale, with one finite positive fp32 scale per tensor.  Rows are addressed as
+ * in hg_suffix_attn (offsets / lengths: DEVICE int32[B]).  Shared levels, Q and the results keep their formats.
+ *   hg_suffix_attn_fp8 / hg_hydragen_attn_fp8: hg_suffix_attn / hg_hydragen_attn over such a cache: the attention
+ *     of the decoded values (the codes are expanded exactly; all arithmetic is fp32).  Rows that no sequence owns
+ *     may hold any code.  The vector-ALU suffix kernel runs whatever HG_OPT_SUFFIX_KERNEL says.
+ *   hg_kv_append_fp8: hg_kv_append with the new bf16 rows quantised on the way in:
+ *     code = nearest E4M3 value to (x / scale) (fp32 quotient), ties to the even code, magnitudes above 448 -> 448.
+ * Invalid scales (zero, negative, infinite, NaN) give HG_ERR_INVALID_ARG.
+ */
+int hg_suffix_attn_fp8(hg_ctx* ctx, const void* Q, const void* Ks8, const void* Vs8, float k_scale, float v_scale,
+                       const int32_t* offsets, const int32_t* lengths, int max_len,
+                       int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype, float* LSE);
+int hg_hydragen_attn_fp8(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* levels,
+                         const void* Ks8, const void* Vs8, float k_scale, float v_scale,
+                         const int32_t* offsets, const int32_t* lengths, int max_len,
+                         int B, int Hq, int Hkv, int D, float scale, void* O_out, int o_dtype, float* LSE_out);
+int hg_kv_append_fp8(hg_ctx* ctx, const void* Knew, const void* Vnew, void* Ks8, void* Vs8, float k_scale, float v_scale,
+                     const int32_t* offsets, int32_t* lengths, int capacity, int B, int Hkv, int D);
+
+/*
  * Non-decomposed comparison (the behaviour Sec. 1 and Sec. 2.3 attribute to per-sequence decode kernels):
  * same arguments and result as hg_hydragen_attn, but every sequence walks its whole key list
  * (shared blocks, then suffix) by itself, so shared rows are re-read once per sequence.

@@ -31,7 +31,7 @@ EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
-    "hg_debug_wide_plan", "hg_debug_suffix_plan",
+    "hg_debug_wide_plan", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
 )
 
 
@@ -97,6 +97,13 @@ def lib() -> ctypes.CDLL:
         L.hg_hydragen_attn_paged.restype = ci
         L.hg_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci]
         L.hg_kv_append.restype = ci
+        L.hg_suffix_attn_fp8.argtypes = [vp, vp, vp, vp, cf, cf, vp, vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
+        L.hg_suffix_attn_fp8.restype = ci
+        L.hg_hydragen_attn_fp8.argtypes = [vp, vp, ci, ctypes.POINTER(hg_level), vp, vp, cf, cf, vp, vp, ci, ci, ci, ci, ci, cf,
+                                           vp, ci, vp]
+        L.hg_hydragen_attn_fp8.restype = ci
+        L.hg_kv_append_fp8.argtypes = [vp, vp, vp, vp, vp, cf, cf, vp, vp, ci, ci, ci, ci]
+        L.hg_kv_append_fp8.restype = ci
         L.hg_kv_append_paged.argtypes = [vp, vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci]
         L.hg_kv_append_paged.restype = ci
         L.hg_debug_wide_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
@@ -367,6 +374,51 @@ def hg_kv_append(ctx: Context, Knew, Vnew, Ks, Vs, offsets, lengths, capacity: i
     _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
     _check(lib().hg_kv_append(ctx.h, _p(Knew), _p(Vnew), _p(Ks), _p(Vs), _p(offsets), _p(lengths), capacity, B, Hkv, D),
            "hg_kv_append")
+
+
+def _want_fp8(Ks8, Vs8, Hkv=None, D=None):
+    _want(Ks8, torch.uint8, name="Ks8"); _want(Vs8, torch.uint8, Ks8.shape, "Vs8")
+    if Ks8.ndim != 3 or (Hkv is not None and tuple(Ks8.shape[1:]) != (Hkv, D)):
+        raise ValueError("Ks8 must be uint8 [T, Hkv, D]")
+
+
+def hg_suffix_attn_fp8(ctx: Context, Q, Ks8, Vs8, k_scale: float, v_scale: float, offsets, lengths, max_len: int, O, LSE,
+                       scale: float = 0.0) -> None:
+    B, Hq, D, lead = _qshape(ctx, Q)
+    _want(Q, torch.bfloat16, name="Q")
+    _want_fp8(Ks8, Vs8)
+    Hkv = Ks8.shape[1]
+    _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _want(O, O.dtype, lead + (D,), "O"); _want(LSE, torch.float32, lead, "LSE")
+    _check(lib().hg_suffix_attn_fp8(ctx.h, _p(Q), _p(Ks8), _p(Vs8), k_scale, v_scale, _p(offsets), _p(lengths), max_len,
+                                    B, Hq, Hkv, D, scale, _p(O), _dtype_code(O), _p(LSE)), "hg_suffix_attn_fp8")
+
+
+def hg_hydragen_attn_fp8(ctx: Context, Q, levels: List[Level], Ks8, Vs8, k_scale: float, v_scale: float, offsets, lengths,
+                         max_len: int, O_out, LSE_out=None, scale: float = 0.0) -> None:
+    B, Hq, D, lead = _qshape(ctx, Q)
+    _want(Q, torch.bfloat16, name="Q")
+    _want_fp8(Ks8, Vs8)
+    Hkv = Ks8.shape[1]
+    for lv in levels:
+        _want(lv.K, torch.bfloat16, name="level K"); _want(lv.V, torch.bfloat16, lv.K.shape, "level V")
+    _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _want(O_out, O_out.dtype, lead + (D,), "O_out")
+    if LSE_out is not None:
+        _want(LSE_out, torch.float32, lead, "LSE_out")
+    n = len(levels)
+    arr = (hg_level * max(n, 1))(*[lv.c_struct() for lv in levels])
+    _check(lib().hg_hydragen_attn_fp8(ctx.h, _p(Q), n, arr, _p(Ks8), _p(Vs8), k_scale, v_scale, _p(offsets), _p(lengths),
+                                      max_len, B, Hq, Hkv, D, scale, _p(O_out), _dtype_code(O_out), _p(LSE_out)),
+           "hg_hydragen_attn_fp8")
+
+
+def hg_kv_append_fp8(ctx: Context, Knew, Vnew, Ks8, Vs8, k_scale: float, v_scale: float, offsets, lengths, capacity: int) -> None:
+    B, Hkv, D = _new_rows(ctx, Knew, Vnew)
+    _want_fp8(Ks8, Vs8, Hkv, D)
+    _want(offsets, torch.int32, (B,), "offsets"); _want(lengths, torch.int32, (B,), "lengths")
+    _check(lib().hg_kv_append_fp8(ctx.h, _p(Knew), _p(Vnew), _p(Ks8), _p(Vs8), k_scale, v_scale, _p(offsets), _p(lengths),
+                                  capacity, B, Hkv, D), "hg_kv_append_fp8")
 
 
 def hg_kv_append_paged(ctx: Context, Knew, Vnew, kv: PagedKV, lengths, capacity: int) -> None:

@@ -165,6 +165,9 @@ int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int nq, 
 
 struct SuffixPlan { int chunk, nchunks, gt; bool mfma; int ipw; };
 
+// Storage format of the suffix cache: bf16 rows, or E4M3 codes with one scale per tensor (value = code * scale).
+struct KvFmt { int fp8 = 0; float k_scale = 1.f, v_scale = 1.f; };
+
 // Work items of the suffix kernel are (sequence, query, KV head, group of query heads, key chunk), one wavefront
 // each, in the vector-ALU kernel, and (sequence, KV head, 32-row tile of the nq * G rows, key chunk) in the
 // matrix-core kernel.  The matrix-core kernel (D = 128, packed rows) takes over when a KV head serves four or more
@@ -173,13 +176,15 @@ struct SuffixPlan { int chunk, nchunks, gt; bool mfma; int ipw; };
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
 // max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30) {
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30,
+                       bool fp8 = false) {
     SuffixPlan p;
     p.gt = pick_gt(G);
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
-    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
+    // an 8-bit cache is read by the vector-ALU kernel only
+    p.mfma = !fp8 && D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
@@ -202,9 +207,13 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
 
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
                const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
-               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0, bool seg = false) {
+               int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0, bool seg = false,
+               const KvFmt& fmt = KvFmt{}) {
     DecodeArgs a{};
     a.pg = pg;
+    a.fp8 = fmt.fp8;
+    a.k_scale = fmt.k_scale;
+    a.v_scale = fmt.v_scale;
     a.Q = static_cast<const uint16_t*>(Q);
     a.n_levels = n_levels;
     for (int i = 0; i < n_levels; ++i) a.lv[i] = lv[i];
@@ -458,7 +467,7 @@ int hg_prefix_attn(hg_ctx* c, const void* Q, const void* Kp, const void* Vp, int
 // hg_suffix_attn and hg_suffix_attn_paged (pg.table set, offsets unused)
 static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs, const int32_t* offsets,
                        const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O, int o_dtype,
-                       float* LSE, const hg::PagedDev& pg, bool paged) {
+                       float* LSE, const hg::PagedDev& pg, bool paged, const KvFmt& fmt = KvFmt{}) {
     if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
     int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
@@ -473,7 +482,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
@@ -482,9 +491,9 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (!p.mfma && p.chunk > max_chunk) return HG_ERR_WORKSPACE;
     if (p.nchunks == 1)
         return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
-                          direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw);
+                          direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw, false, fmt);
     rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
-                    parts_out(parts, 0), s, pg, p.mfma, p.ipw);
+                    parts_out(parts, 0), s, pg, p.mfma, p.ipw, false, fmt);
     if (rc) return rc;
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
 }
@@ -564,7 +573,7 @@ static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* l
 // hg_hydragen_attn and hg_hydragen_attn_paged (pg.table set, offsets unused)
 static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
                       const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
-                      float scale, void* O_out, int o_dtype, float* LSE_out, const hg::PagedDev& pg) {
+                      float scale, void* O_out, int o_dtype, float* LSE_out, const hg::PagedDev& pg, const KvFmt& fmt = KvFmt{}) {
     int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype,
                          pg.table != nullptr);
     if (rc) return rc;
@@ -593,7 +602,8 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
             const long long tiles = (seqs * nq * G + kPrefixRowsWide - 1) / kPrefixRowsWide;
             if (seqs * nq * G > kPrefixRowsNarrow && tiles <= 32 && tiles > T) T = (int)tiles;
         }
-        const double bytes = 4.0 * B * nq * (0.75 * max_len) * Hkv * D;   // K and V, bf16; mean length taken as 0.75 max_len
+        // K and V, bf16 (or 8-bit codes); mean length taken as 0.75 max_len
+        const double bytes = (fmt.fp8 ? 2.0 : 4.0) * B * nq * (0.75 * max_len) * Hkv * D;
         wide_slots = pick_wide_slots(flops, bytes, T);
         tiny = c->opt_overlap == 0 && flops / 1.14e15 + bytes / 6.0e12 < 60e-6;
         if (tiny) wide_slots = 32;
@@ -607,7 +617,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         ++nlev;
     }
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
@@ -667,7 +677,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
         const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, sp.chunk,
-                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg, sp.mfma, sp.ipw);
+                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg, sp.mfma, sp.ipw, false, fmt);
         if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
@@ -731,7 +741,7 @@ int hg_hydragen_attn_paged(hg_ctx* c, const void* Q, int n_levels, const hg_leve
 
 // hg_kv_append and hg_kv_append_paged
 static int append_impl(hg_ctx* c, const void* Knew, const void* Vnew, void* Ks, void* Vs, const int32_t* offsets,
-                       int32_t* lengths, int capacity, int B, int Hkv, int D, const hg::PagedDev& pg) {
+                       int32_t* lengths, int capacity, int B, int Hkv, int D, const hg::PagedDev& pg, const KvFmt& fmt = KvFmt{}) {
     if (!c || B < 0 || Hkv <= 0 || capacity < 0) return HG_ERR_INVALID_ARG;
     if (D != 64 && D != 128) return HG_ERR_UNSUPPORTED;
     if ((int64_t)B * c->opt_nq * Hkv * D >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
@@ -752,6 +762,9 @@ static int append_impl(hg_ctx* c, const void* Knew, const void* Vnew, void* Ks, 
     a.B = B;
     a.nq = c->opt_nq;
     a.row_elems = Hkv * D;
+    a.fp8 = fmt.fp8;
+    a.k_scale = fmt.k_scale;
+    a.v_scale = fmt.v_scale;
     return hip_rc(hg::launch_kv_append(a, c->stream));
 }
 
@@ -768,6 +781,39 @@ int hg_kv_append_paged(hg_ctx* c, const void* Knew, const void* Vnew, const hg_p
     if (rc) return rc;
     if (capacity == 0) return HG_OK;
     return append_impl(c, Knew, Vnew, kv->K, kv->V, nullptr, lengths, capacity, B, Hkv, D, pg);
+}
+
+// scales of an 8-bit cache: finite and positive
+static bool fp8_fmt(float k_scale, float v_scale, KvFmt* out) {
+    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3.0e38f || v_scale > 3.0e38f) return false;
+    out->fp8 = 1;
+    out->k_scale = k_scale;
+    out->v_scale = v_scale;
+    return true;
+}
+
+int hg_suffix_attn_fp8(hg_ctx* c, const void* Q, const void* Ks8, const void* Vs8, float k_scale, float v_scale,
+                       const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale,
+                       void* O, int o_dtype, float* LSE) {
+    KvFmt fmt;
+    if (!fp8_fmt(k_scale, v_scale, &fmt)) return HG_ERR_INVALID_ARG;
+    return suffix_impl(c, Q, Ks8, Vs8, offsets, lengths, max_len, B, Hq, Hkv, D, scale, O, o_dtype, LSE, hg::PagedDev{}, false, fmt);
+}
+
+int hg_hydragen_attn_fp8(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks8, const void* Vs8,
+                         float k_scale, float v_scale, const int32_t* offsets, const int32_t* lengths, int max_len, int B,
+                         int Hq, int Hkv, int D, float scale, void* O_out, int o_dtype, float* LSE_out) {
+    KvFmt fmt;
+    if (!fp8_fmt(k_scale, v_scale, &fmt)) return HG_ERR_INVALID_ARG;
+    return fused_impl(c, Q, n_levels, levels, Ks8, Vs8, offsets, lengths, max_len, B, Hq, Hkv, D, scale, O_out, o_dtype,
+                      LSE_out, hg::PagedDev{}, fmt);
+}
+
+int hg_kv_append_fp8(hg_ctx* c, const void* Knew, const void* Vnew, void* Ks8, void* Vs8, float k_scale, float v_scale,
+                     const int32_t* offsets, int32_t* lengths, int capacity, int B, int Hkv, int D) {
+    KvFmt fmt;
+    if (!fp8_fmt(k_scale, v_scale, &fmt)) return HG_ERR_INVALID_ARG;
+    return append_impl(c, Knew, Vnew, Ks8, Vs8, offsets, lengths, capacity, B, Hkv, D, hg::PagedDev{}, fmt);
 }
 
 int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,

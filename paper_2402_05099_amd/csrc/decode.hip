@@ -4,6 +4,12 @@
 // kernels do: every sequence re-reads the shared rows).  Memory-bound: one wavefront per work item
 // (sequence, KV head, group of GT query heads, key chunk), 16-byte bf16 loads, fp32 arithmetic on the
 // vector ALU, DPP reductions inside the 16-lane row that holds one key.
+// FP8 = true (suffix rows only, packed): the cache holds 8-bit E4M3 codes with one fp32 scale per tensor (not in the
+// paper: half the bytes for the part of the method that is bound by them).  The same lanes own the same 8 columns,
+// fetched with 8-byte loads and converted two at a time by the hardware; the K scale is folded into the query, the
+// V scale into the final normalisation.
+#include <type_traits>
+
 #include "hg_internal.h"
 
 namespace hg {
@@ -39,9 +45,10 @@ struct DecodeState {
 };
 
 // One batch of U wave-wide loads: KPW keys each, K and V rows of this lane's 8-column slice.
-template <int D, int U>
+template <int D, int U, bool FP8>
 struct KVBatch {
-    uint4 k[U], v[U];
+    using Row = std::conditional_t<FP8, uint2, uint4>;   // this lane's 8 elements of a row
+    Row k[U], v[U];
 };
 
 // 16-byte load from global memory at uniform base + 32-bit lane offset (scalar base register + vector offset form)
@@ -55,13 +62,38 @@ __device__ __forceinline__ uint4 ldg128(const unsigned char* base, unsigned off)
     const u32x4 v = STREAM ? __builtin_nontemporal_load(p) : *p;
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <bool STREAM>
+__device__ __forceinline__ uint2 ldg64(const unsigned char* base, unsigned off) {
+    const auto* p = reinterpret_cast<const __attribute__((address_space(1))) u32x2*>(
+        (const __attribute__((address_space(1))) unsigned char*)base + off);
+    const u32x2 v = STREAM ? __builtin_nontemporal_load(p) : *p;
+    return make_uint2(v.x, v.y);
+}
+template <bool STREAM, bool FP8>
+__device__ __forceinline__ auto ldg_row(const unsigned char* base, unsigned off) {
+    if constexpr (FP8) return ldg64<STREAM>(base, off);
+    else return ldg128<STREAM>(base, off);
+}
+
+// this lane's 8 elements of a row as fp32
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8]) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+}
+__device__ __forceinline__ void unpack8(const uint2& r, float (&f)[8]) {
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, true);
+    f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y; f[4] = c.x; f[5] = c.y; f[6] = d.x; f[7] = d.y;
+}
 
 // kb/vb: wavefront-uniform byte pointers to the span's first row of this KV head; rowoff: this lane's byte offset
 // of its key in load 0 of the batch (sub-row, column slice and batch start); colb: the column part alone.  Lanes
 // whose key lies past the span read the span's first row instead (always valid; their score is masked), so no
 // load is predicated and a batch may be requested past the end of the span.
-template <int D, int U, bool STREAM>
-__device__ __forceinline__ void load_batch(KVBatch<D, U>& bt, const unsigned char* __restrict__ kb,
+template <int D, int U, bool STREAM, bool FP8>
+__device__ __forceinline__ void load_batch(KVBatch<D, U, FP8>& bt, const unsigned char* __restrict__ kb,
                                            const unsigned char* __restrict__ vb, unsigned rstride_b, unsigned rowoff,
                                            unsigned colb, int first, int n) {
     constexpr int KPW = 64 / (D / 8);
@@ -69,33 +101,27 @@ __device__ __forceinline__ void load_batch(KVBatch<D, U>& bt, const unsigned cha
     for (int u = 0; u < U; ++u) {
         const int i = first + u * KPW;   // `first` already includes this lane's sub-row
         const unsigned off = i < n ? (unsigned)(u * KPW) * rstride_b + rowoff : colb;
-        bt.k[u] = ldg128<STREAM>(kb, off);
-        bt.v[u] = ldg128<STREAM>(vb, off);
+        bt.k[u] = ldg_row<STREAM, FP8>(kb, off);
+        bt.v[u] = ldg_row<STREAM, FP8>(vb, off);
     }
 }
 
 // online-softmax update of the state with one batch (keys first + u*KPW, masked beyond n)
-template <int D, int GT, int U>
-__device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBatch<D, U>& bt, int first, int n) {
+template <int D, int GT, int U, bool FP8>
+__device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBatch<D, U, FP8>& bt, int first, int n) {
     constexpr int LPR = D / 8;
     constexpr int KPW = 64 / LPR;
     float s[U][GT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const bool ok = first + u * KPW < n;
-        const uint4 kr = bt.k[u];
-        const float k0 = bf16_lo(kr.x), k1 = bf16_hi(kr.x), k2 = bf16_lo(kr.y), k3 = bf16_hi(kr.y);
-        const float k4 = bf16_lo(kr.z), k5 = bf16_hi(kr.z), k6 = bf16_lo(kr.w), k7 = bf16_hi(kr.w);
+        float k[8];
+        unpack8(bt.k[u], k);
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            float d = st.q[g][0] * k0;
-            d = fmaf(st.q[g][1], k1, d);
-            d = fmaf(st.q[g][2], k2, d);
-            d = fmaf(st.q[g][3], k3, d);
-            d = fmaf(st.q[g][4], k4, d);
-            d = fmaf(st.q[g][5], k5, d);
-            d = fmaf(st.q[g][6], k6, d);
-            d = fmaf(st.q[g][7], k7, d);
+            float d = st.q[g][0] * k[0];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) d = fmaf(st.q[g][j], k[j], d);
             d = row_allreduce_sum<LPR>(d);
             s[u][g] = ok ? d : -INFINITY;
         }
@@ -120,15 +146,10 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBa
         for (int j = 0; j < 8; ++j) st.acc[g][j] *= alpha;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint4 vr = bt.v[u];
-            st.acc[g][0] = fmaf(p[u], bf16_lo(vr.x), st.acc[g][0]);
-            st.acc[g][1] = fmaf(p[u], bf16_hi(vr.x), st.acc[g][1]);
-            st.acc[g][2] = fmaf(p[u], bf16_lo(vr.y), st.acc[g][2]);
-            st.acc[g][3] = fmaf(p[u], bf16_hi(vr.y), st.acc[g][3]);
-            st.acc[g][4] = fmaf(p[u], bf16_lo(vr.z), st.acc[g][4]);
-            st.acc[g][5] = fmaf(p[u], bf16_hi(vr.z), st.acc[g][5]);
-            st.acc[g][6] = fmaf(p[u], bf16_lo(vr.w), st.acc[g][6]);
-            st.acc[g][7] = fmaf(p[u], bf16_hi(vr.w), st.acc[g][7]);
+            float v[8];
+            unpack8(bt.v[u], v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st.acc[g][j] = fmaf(p[u], v[j], st.acc[g][j]);
         }
     }
 }
@@ -136,7 +157,7 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBa
 // Online-softmax pass over `n` consecutive KV rows starting at row0, KV head kvh.  Software pipelined: the
 // loads of the next batch are issued before the current batch is consumed, so a wavefront always has a
 // batch in flight while it computes.
-template <int D, int GT, bool STREAM>
+template <int D, int GT, bool STREAM, bool FP8 = false>
 __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
                                             const uint16_t* __restrict__ V, int64_t row0, int n, int Hkv, int kvh,
                                             int lane) {
@@ -144,27 +165,29 @@ __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16
     constexpr int KPW = 64 / LPR;
     constexpr int U = GT >= 8 ? 2 : 4;
     constexpr int STEP = KPW * U;
+    constexpr unsigned ES = FP8 ? 1u : 2u;     // bytes per element
     const int sub = lane / LPR;
-    const unsigned rstride_b = (unsigned)Hkv * D * 2u;
-    const unsigned colb = (unsigned)(lane % LPR) * 16u;
+    const unsigned rstride_b = (unsigned)Hkv * D * ES;
+    const unsigned colb = (unsigned)(lane % LPR) * 8u * ES;
     unsigned rowoff = (unsigned)sub * rstride_b + colb;
-    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K + (row0 * Hkv + kvh) * (int64_t)D));
-    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V + (row0 * Hkv + kvh) * (int64_t)D));
+    const int64_t first_b = (row0 * Hkv + kvh) * (int64_t)D * ES;
+    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K) + first_b);
+    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V) + first_b);
     const unsigned step_b = (unsigned)STEP * rstride_b;
 
     // every load is issued unconditionally (see load_batch), so the wait counts the compiler derives are exact
-    KVBatch<D, U> ba, bb;
-    load_batch<D, U, STREAM>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
+    KVBatch<D, U, FP8> ba, bb;
+    load_batch<D, U, STREAM, FP8>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
     for (int it = 0; it < n; it += 2 * STEP) {
         rowoff += step_b;
-        load_batch<D, U, STREAM>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
+        load_batch<D, U, STREAM, FP8>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic that hides their latency
-        consume_batch<D, GT, U>(st, ba, it + sub, n);
+        consume_batch<D, GT, U, FP8>(st, ba, it + sub, n);
         rowoff += step_b;
         __builtin_amdgcn_sched_barrier(0);
-        load_batch<D, U, STREAM>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
+        load_batch<D, U, STREAM, FP8>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + STEP < n) consume_batch<D, GT, U>(st, bb, it + STEP + sub, n);
+        if (it + STEP < n) consume_batch<D, GT, U, FP8>(st, bb, it + STEP + sub, n);
     }
 }
 
@@ -200,7 +223,7 @@ __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const 
         return ((unsigned)(page << shift) + (unsigned)(pos & ((1 << shift) - 1))) * rstride_b;
     };
     const unsigned safe = row_base(0) + colb;   // lanes past the span read its first row (their scores are masked)
-    auto load = [&](KVBatch<D, U>& bt, int i0) {
+    auto load = [&](KVBatch<D, U, false>& bt, int i0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int iu = i0 + u * KPW;
@@ -210,16 +233,16 @@ __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const 
         }
     };
 
-    KVBatch<D, U> ba, bb;
+    KVBatch<D, U, false> ba, bb;
     load(ba, 0);
     for (int it = 0; it < n; it += 2 * STEP) {
         load(bb, it + STEP);
         __builtin_amdgcn_sched_barrier(0);
-        consume_batch<D, GT, U>(st, ba, it + sub, n);
+        consume_batch<D, GT, U, false>(st, ba, it + sub, n);
         __builtin_amdgcn_sched_barrier(0);
         load(ba, it + 2 * STEP);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + STEP < n) consume_batch<D, GT, U>(st, bb, it + STEP + sub, n);
+        if (it + STEP < n) consume_batch<D, GT, U, false>(st, bb, it + STEP + sub, n);
     }
 }
 
@@ -248,7 +271,8 @@ __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& 
 // SHARED = false: suffix rows only (the Hydragen suffix part).  SHARED = true: the shared blocks of every level
 // are walked too (the non-decomposed comparison); a separate instantiation so that profiles tell them apart.
 // PAGED (only without SHARED): the suffix rows are read through a page table.
-template <int D, int GT, bool SHARED, bool PAGED>
+// FP8 (only without SHARED and PAGED): the suffix rows are E4M3 codes; a key is code * a.k_scale, a value code * a.v_scale.
+template <int D, int GT, bool SHARED, bool PAGED, bool FP8 = false>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     constexpr int LPR = D / 8;
     const int lane = threadIdx.x & 63;
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
 
     DecodeState<D, GT> st;
     {
-        const float qs = a.scale * kLog2e;
+        const float qs = FP8 ? a.scale * kLog2e * a.k_scale : a.scale * kLog2e;
         const int col = (lane % LPR) * 8;
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
@@ -299,7 +323,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
         if (s0 < s1) {
             if constexpr (PAGED) decode_span_paged<D, GT>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
-            else decode_span<D, GT, true>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+            else decode_span<D, GT, true, FP8>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
         }
     }
 
@@ -322,7 +346,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
             for (int off = LPR; off < 64; off <<= 1) o[j] += __shfl_xor(o[j], off);
         }
         if (lane < LPR) {
-            const float inv = l > 0.f ? 1.0f / l : 0.f;
+            const float inv = l > 0.f ? (FP8 ? a.v_scale / l : 1.0f / l) : 0.f;
             const int64_t idx = (int64_t)bq * a.Hq + h0 + g;
             const int64_t e = (int64_t)c * a.out.part_stride_O + idx * D + lane * 8;
             if (a.out.bf16) {
@@ -346,7 +370,10 @@ static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     if (a.units == 0) return hipSuccess;
     const int64_t grid = (a.units + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (a.pg.table) {
+    if (a.fp8) {
+        if (a.n_levels > 0 || a.pg.table) return hipErrorInvalidValue;   // 8-bit rows: packed suffix only
+        decode_kernel<D, GT, false, false, true><<<(unsigned)grid, 256, 0, s>>>(a);
+    } else if (a.pg.table) {
         if (a.n_levels > 0) return hipErrorInvalidValue;   // the comparison kernel has no paged form
         decode_kernel<D, GT, false, true><<<(unsigned)grid, 256, 0, s>>>(a);
     } else if (a.n_levels > 0) {

@@ -334,3 +334,41 @@ def new_rows(w: Workload, step: int = 0):
     """(Knew, Vnew) uint16 [B, Hkv, D] (or [B, nq, Hkv, D]): the K/V rows of the tokens a decode step adds (tensor ids 120+2*step, 121+2*step)."""
     shape = (w.B, w.Hkv, w.D) if w.nq == 1 else (w.B, w.nq, w.Hkv, w.D)
     return normal_bf16(w.seed, 120 + 2 * step, shape), normal_bf16(w.seed, 121 + 2 * step, shape)
+
+
+@dataclass
+class Fp8Suffix:
+    """An 8-bit suffix cache for a workload: E4M3 codes, one scale per tensor (value = code * scale)."""
+    Ks8: np.ndarray        # uint8 [T, Hkv, D]
+    Vs8: np.ndarray
+    k_scale: float
+    v_scale: float
+    offsets: np.ndarray    # int32 [B]
+    capacity: int          # rows every sequence may hold
+
+
+def make_fp8(w: Workload, reserve: int = 0, headroom: float = 1.0, junk_code: Optional[int] = 0x7F) -> Fp8Suffix:
+    """w's suffix rows as an 8-bit cache with room for `reserve` more rows per sequence.
+
+    Scales are per-tensor calibration values: largest magnitude * headroom / 448 (headroom < 1 makes the largest values
+    saturate).  The codes come from torch's float8_e4m3fn conversion of value / scale (a library routine: this module
+    holds no arithmetic of the method).  Rows no sequence owns hold `junk_code` (0x7f is a NaN code; None: zero).
+    """
+    import torch
+
+    cap = w.max_len + reserve
+    offsets = (np.arange(w.B, dtype=np.int64) * cap).astype(np.int32)
+    out = []
+    scales = []
+    for bits in (w.Ks, w.Vs):
+        x = bf16_bits_to_f32(bits)
+        amax = float(np.abs(x).max()) if x.size else 1.0
+        scale = float(np.float32(max(amax, 1e-6) * headroom / 448.0))
+        q = torch.from_numpy(x / np.float32(scale)).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        full = np.full((w.B * cap, w.Hkv, w.D), 0 if junk_code is None else junk_code, dtype=np.uint8)
+        for b in range(w.B):
+            n = int(w.lengths[b])
+            full[offsets[b]: offsets[b] + n] = q[w.offsets[b]: w.offsets[b] + n]
+        out.append(full)
+        scales.append(scale)
+    return Fp8Suffix(Ks8=out[0], Vs8=out[1], k_scale=scales[0], v_scale=scales[1], offsets=offsets, capacity=cap)

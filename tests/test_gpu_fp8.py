@@ -1,0 +1,251 @@
+"""GPU parity of the 8-bit (E4M3) suffix cache: suffix attention and the fused call over such a cache against the fp64
+oracle on the decoded values, and the quantising cache update against the oracle's codes, bit for bit."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import fp8
+from paper_2402_05099_amd import binding as hb
+from paper_2402_05099_amd import device as dev
+from paper_2402_05099_amd import workloads as wl
+from parity import check, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def u8(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def i32(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda:0")
+
+
+def finite_codes(n_rows: int) -> np.ndarray:
+    """[n_rows, 2, 128]: every row holds all 256 codes in order (heads 0 and 1), the two NaN codes replaced by 0x3a."""
+    row = np.arange(256, dtype=np.uint8)
+    row[(row & 0x7F) == 0x7F] = 0x3A
+    return np.broadcast_to(row.reshape(1, 2, 128), (n_rows, 2, 128)).copy()
+
+
+def test_every_value_code_is_decoded_exactly():
+    """One key per sequence, so the softmax weight is exactly 1 and O = decode(V code) * v_scale, one fp32 product."""
+    say("fp8 decode of every V code")
+    B, H, D = 3, 2, 128
+    Vs8 = finite_codes(B)
+    Ks8 = np.full((B, H, D), 0x38, dtype=np.uint8)
+    Q = dev.bf16_tensor(wl.normal_bf16(1, 0, (B, H, D)), "cuda:0")
+    offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
+    ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
+    O = torch.full((B, H, D), float("nan"), dtype=torch.float32, device="cuda:0")
+    L = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda:0")
+    v_scale = 0.37
+    hb.hg_suffix_attn_fp8(ctx, Q, u8(Ks8), u8(Vs8), 0.5, v_scale, offsets, lengths, 1, O, L)
+    torch.cuda.synchronize()
+    want = fp8.e4m3_decode(Vs8).astype(np.float32) * np.float32(v_scale)
+    assert np.array_equal(O.cpu().numpy(), want)
+    ctx.close()
+
+
+def test_every_key_code_is_decoded_exactly():
+    """One key per sequence and a one-hot query: LSE is the single score q_d * decode(K code) * k_scale * scale."""
+    say("fp8 decode of every K code")
+    B, H, D = 128, 2, 128
+    Ks8 = finite_codes(B)
+    Vs8 = np.full((B, H, D), 0x38, dtype=np.uint8)
+    q = np.zeros((B, H, D), dtype=np.float32)
+    for b in range(B):
+        q[b, :, b] = 2.0
+    Q = dev.bf16_tensor(wl.f32_to_bf16_bits(q), "cuda:0")
+    offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
+    ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
+    O = torch.empty((B, H, D), dtype=torch.float32, device="cuda:0")
+    L = torch.empty((B, H), dtype=torch.float32, device="cuda:0")
+    k_scale, scale = 0.75, 0.25
+    hb.hg_suffix_attn_fp8(ctx, Q, u8(Ks8), u8(Vs8), k_scale, 1.0, offsets, lengths, 1, O, L, scale)
+    torch.cuda.synchronize()
+    vals = fp8.e4m3_decode(Ks8[0])                                  # [2, 128]
+    want = 2.0 * vals.T * k_scale * scale                           # [B = d, H]
+    got = L.cpu().numpy().astype(np.float64)
+    assert np.allclose(got, want, rtol=2e-6, atol=1e-9), float(np.abs(got - want).max())
+    assert np.array_equal(O.cpu().numpy(), np.ones((B, H, D), dtype=np.float32))
+    ctx.close()
+
+
+CASES = {
+    "tiny_d64": dict(idx=1),
+    "mha": dict(idx=2),
+    "ragged": dict(idx=3),
+    "gqa8": dict(idx=4),
+    "tree": dict(idx=5),
+    "one_kv_head": dict(idx=6),
+    "ragged_nq3": dict(idx=3, nq=3),
+}
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("chunk", [0, 64], ids=["auto", "chunk64"])
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_suffix_attn_fp8(case, chunk, out_dtype):
+    say(f"fp8 suffix {case} chunk={chunk} {out_dtype}")
+    kw = dict(CASES[case])
+    w = wl.scaled_down(kw.pop("idx"), **kw)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w, reserve=5)                  # unowned rows hold a NaN code
+    ctx = dev.make_context(dw, parts=24)
+    if chunk:
+        ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
+    Oref, Lref = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
+    O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=out_dtype, device="cuda:0")
+    L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+    hb.hg_suffix_attn_fp8(ctx, dw.Q, u8(f8.Ks8), u8(f8.Vs8), f8.k_scale, f8.v_scale, i32(f8.offsets), dw.lengths, dw.max_len,
+                          O, L, dw.scale)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, f"fp8 suffix {case}", out_bf16=out_dtype == torch.bfloat16)
+    ctx.close()
+
+
+def test_suffix_attn_fp8_saturated_cache_and_small_workspace():
+    """Scales so small that the largest values saturate at 448, and a workspace with room for two partial results."""
+    say("fp8 suffix saturated")
+    w = wl.scaled_down(3)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w, headroom=0.5, junk_code=None)
+    assert (f8.Ks8 & 0x7F).max() == 0x7E and ((f8.Ks8 & 0x7F) == 0x7E).sum() > 10
+    ctx = dev.make_context(dw, parts=2)
+    Oref, Lref = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
+    O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+    L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+    hb.hg_suffix_attn_fp8(ctx, dw.Q, u8(f8.Ks8), u8(f8.Vs8), f8.k_scale, f8.v_scale, i32(f8.offsets), dw.lengths, dw.max_len,
+                          O, L, dw.scale)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, "fp8 suffix saturated")
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["mha", "ragged", "gqa8", "tree", "ragged_nq3"])
+def test_hydragen_attn_fp8(case):
+    """Fused call: bf16 shared levels, 8-bit suffix.  Oracle: the merge (Eq. 5) of the exact attention over the levels
+    and the exact attention over the decoded suffix."""
+    say(f"fp8 fused {case}")
+    kw = dict(CASES[case])
+    w = wl.scaled_down(kw.pop("idx"), **kw)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w, reserve=3)
+    ctx = dev.make_context(dw, parts=24)
+    Op, Lp = oracle.attention(w, suffix=False)
+    Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
+    Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
+    O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+    hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, u8(f8.Ks8), u8(f8.Vs8), f8.k_scale, f8.v_scale, i32(f8.offsets), dw.lengths,
+                            dw.max_len, O, L, dw.scale)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Oref, Lref, f"fp8 fused {case}", out_bf16=True)
+    ctx.close()
+
+
+def special_rows(shape, scale: float, seed: int) -> np.ndarray:
+    """bf16 bit patterns: N(0, 1) * 40 * scale values with, sprinkled in, every tie between neighbouring codes (times the
+    scale, which is a power of two so that the quotient is the tie again), values beyond the largest code, values that
+    round to zero and to the smallest subnormal, both zeros and a NaN."""
+    rng = np.random.default_rng(seed)
+    x = (rng.normal(0, 40.0, shape) * scale).astype(np.float32)
+    grid = fp8.e4m3_decode(np.arange(127, dtype=np.uint8))
+    ties = (grid[:-1] + grid[1:]) / 2
+    extra = np.concatenate([ties, -ties, [449.0, 464.0, 480.0, 1e6, -1e6, 2.0 ** -10, 2.0 ** -11, 1.5 * 2.0 ** -10,
+                                          0.0, -0.0, np.nan, 448.0, -448.0, 2.0 ** -9]]) * scale
+    flat = x.reshape(-1)
+    pos = rng.choice(flat.shape[0], size=extra.shape[0], replace=False)
+    flat[pos] = extra.astype(np.float32)
+    bits = wl.f32_to_bf16_bits(flat.reshape(shape))
+    return bits
+
+
+@pytest.mark.parametrize("nq", [1, 3])
+def test_kv_append_fp8_codes_bit_for_bit(nq):
+    say(f"fp8 append nq={nq}")
+    w = wl.scaled_down(3, nq=nq)
+    f8 = wl.make_fp8(w, reserve=4, junk_code=None)
+    cap = f8.capacity
+    k_scale, v_scale = 0.125, 2.0            # powers of two: ties stay ties, and every tie is a bf16 value
+    lengths = w.lengths.copy()
+    lengths[0] = cap                          # full: nothing fits
+    lengths[1] = cap - 1                      # room for one row only
+    shape = (w.B, w.Hkv, w.D) if nq == 1 else (w.B, nq, w.Hkv, w.D)
+    Knew, Vnew = special_rows(shape, k_scale, 21), special_rows(shape, v_scale, 22)
+    Kd, Vd, Ld = u8(f8.Ks8), u8(f8.Vs8), i32(lengths)
+    ctx = hb.Context(0, hb.hg_workspace_bytes(w.B * nq, w.Hq, w.D, 4))
+    ctx.set_option(hb.HG_OPT_NUM_QUERIES, nq)
+    hb.hg_kv_append_fp8(ctx, dev.bf16_tensor(Knew, "cuda:0"), dev.bf16_tensor(Vnew, "cuda:0"), Kd, Vd, k_scale, v_scale,
+                        i32(f8.offsets), Ld, cap)
+    torch.cuda.synchronize()
+    Kref, Vref, Lref = fp8.kv_append_fp8(f8.Ks8, f8.Vs8, f8.offsets, lengths, cap, wl.bf16_bits_to_f32(Knew),
+                                         wl.bf16_bits_to_f32(Vnew), k_scale, v_scale)
+    assert np.array_equal(Ld.cpu().numpy(), Lref)
+    for got, ref in ((Kd.cpu().numpy(), Kref), (Vd.cpu().numpy(), Vref)):
+        nan = (ref & 0x7F) == 0x7F
+        assert nan.sum() >= 1
+        assert np.array_equal(got[~nan], ref[~nan])
+        assert ((got[nan] & 0x7F) == 0x7F).all()
+    ctx.close()
+
+
+def test_decode_steps_on_an_8bit_cache():
+    """Append, then attend, three times: the cache the device maintains gives the oracle's attention over the oracle's cache."""
+    say("fp8 decode steps")
+    w = wl.scaled_down(5)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w, reserve=3, junk_code=None)
+    cap = f8.capacity
+    Kd, Vd, Ld, offs = u8(f8.Ks8), u8(f8.Vs8), i32(w.lengths), i32(f8.offsets)
+    Kh, Vh, Lh = f8.Ks8, f8.Vs8, w.lengths.copy()
+    ctx = dev.make_context(dw, parts=24)
+    Op, Lp = oracle.attention(w, suffix=False)
+    for step in range(3):
+        Knew, Vnew = wl.new_rows(w, step)
+        hb.hg_kv_append_fp8(ctx, dev.bf16_tensor(Knew, "cuda:0"), dev.bf16_tensor(Vnew, "cuda:0"), Kd, Vd, f8.k_scale,
+                            f8.v_scale, offs, Ld, cap)
+        O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+        L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+        hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, Kd, Vd, f8.k_scale, f8.v_scale, offs, Ld, cap, O, L, dw.scale)
+        torch.cuda.synchronize()
+        Kh, Vh, Lh = fp8.kv_append_fp8(Kh, Vh, f8.offsets, Lh, cap, wl.bf16_bits_to_f32(Knew), wl.bf16_bits_to_f32(Vnew),
+                                       f8.k_scale, f8.v_scale)
+        assert np.array_equal(Ld.cpu().numpy(), Lh)
+        assert np.array_equal(Kd.cpu().numpy(), Kh) and np.array_equal(Vd.cpu().numpy(), Vh)
+        Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, Kh, Vh, f8.k_scale, f8.v_scale, f8.offsets, Lh, w.scale)
+        Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
+        check(to_np(O), to_np(L), Oref, Lref, f"fp8 decode step {step}")
+    ctx.close()
+
+
+def test_fp8_error_paths():
+    say("fp8 errors")
+    w = wl.scaled_down(1)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w)
+    ctx = dev.make_context(dw, parts=4)
+    O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+    L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+    K8, V8, offs = u8(f8.Ks8), u8(f8.Vs8), i32(f8.offsets)
+    for ks, vs in ((0.0, 1.0), (1.0, -1.0), (float("nan"), 1.0), (1.0, float("inf"))):
+        with pytest.raises(hb.HydragenError) as e:
+            hb.hg_suffix_attn_fp8(ctx, dw.Q, K8, V8, ks, vs, offs, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert e.value.code == hb.HG_ERR_INVALID_ARG
+        with pytest.raises(hb.HydragenError):
+            hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, K8, V8, ks, vs, offs, dw.lengths, dw.max_len, O, L, dw.scale)
+        with pytest.raises(hb.HydragenError):
+            Knew, Vnew = wl.new_rows(w, 0)
+            hb.hg_kv_append_fp8(ctx, dev.bf16_tensor(Knew, "cuda:0"), dev.bf16_tensor(Vnew, "cuda:0"), K8, V8, ks, vs, offs,
+                                dw.lengths.clone(), f8.capacity)
+    with pytest.raises(TypeError):
+        hb.hg_suffix_attn_fp8(ctx, dw.Q, dw.Ks, dw.Vs, 1.0, 1.0, offs, dw.lengths, dw.max_len, O, L, dw.scale)   # bf16 cache
+    ctx.close()
