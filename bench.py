@@ -54,6 +54,7 @@ def main() -> int:
                     help="also run one plain device-to-device copy of this many MiB (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--prefix-kernel", type=int, default=0, help="0 auto, 1 128-row workgroups, 2 256-row workgroups")
     ap.add_argument("--paged", type=int, default=0, help="rows per page: the suffix cache is a page pool read through a page table (0 = packed rows, the default)")
+    ap.add_argument("--fp8-kv", action="store_true", help="the suffix cache holds 8-bit E4M3 codes with one scale per tensor (hg_hydragen_attn_fp8); a variant, not the headline")
     ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
     ap.add_argument("--suffix-kernel", type=int, default=0, help="HG_OPT_SUFFIX_KERNEL: 0 automatic, 1 vector-ALU, 2 matrix-core")
     ap.add_argument("--graph", action="store_true", help="also time the fused call replayed from a captured HIP graph (reported as graph_ms_per_step; the headline stays the eager call)")
@@ -102,8 +103,19 @@ def main() -> int:
         kv = dev.paged_to_device(wl.make_paged(w, args.paged, reserve=args.append_steps))
         torch.cuda.synchronize()
 
+    f8 = None
+    if args.fp8_kv:
+        if args.paged:
+            raise SystemExit("--fp8-kv needs packed rows (no --paged)")
+        f8 = wl.make_fp8(w, reserve=args.append_steps, junk_code=None)
+        dK8, dV8 = torch.from_numpy(f8.Ks8).cuda(), torch.from_numpy(f8.Vs8).cuda()
+        doff8 = torch.from_numpy(f8.offsets).cuda()
+        torch.cuda.synchronize()
+
     def step():
-        if kv is not None:
+        if f8 is not None:
+            hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, dK8, dV8, f8.k_scale, f8.v_scale, doff8, dw.lengths, dw.max_len, O, L, dw.scale)
+        elif kv is not None:
             hb.hg_hydragen_attn_paged(ctx, dw.Q, dw.levels, kv, dw.lengths, dw.max_len, O, L, dw.scale)
         else:
             hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
@@ -172,7 +184,8 @@ def main() -> int:
     B, Hq, Hkv, D, G = w.B, w.Hq, w.Hkv, w.D, w.G
     rows = B * Hq
     T = int(np.minimum(w.lengths, w.max_len).sum())
-    suffix_bytes = 4 * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
+    kv_elem = 1 if f8 is not None else 2
+    suffix_bytes = 2 * kv_elem * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
     level_flops, level_bytes = [], []
     for lv in w.levels:
         f = by = 0
@@ -229,7 +242,9 @@ def main() -> int:
         dKn, dVn = dev.bf16_tensor(Kn, "cuda:0"), dev.bf16_tensor(Vn, "cuda:0")
         dlen = dw.lengths.clone()
         cap = w.max_len + args.append_steps
-        if kv is None:
+        if f8 is not None:
+            dK, dV, doff, cap = dK8, dV8, doff8, f8.capacity
+        elif kv is None:
             hK, hV, hoff, cap = wl.with_room(w, args.append_steps)
             dK, dV, doff = dev.bf16_tensor(hK, "cuda:0"), dev.bf16_tensor(hV, "cuda:0"), torch.from_numpy(hoff).cuda()
             del hK, hV
@@ -237,7 +252,9 @@ def main() -> int:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(args.append_steps):
-            if kv is not None:
+            if f8 is not None:
+                hb.hg_kv_append_fp8(ctx, dKn, dVn, dK, dV, f8.k_scale, f8.v_scale, doff, dlen, cap)
+            elif kv is not None:
                 hb.hg_kv_append_paged(ctx, dKn, dVn, kv, dlen, cap)
             else:
                 hb.hg_kv_append(ctx, dKn, dVn, dK, dV, doff, dlen, cap)
@@ -258,6 +275,14 @@ def main() -> int:
         c0 = time.perf_counter()
         Oref, Lref = oracle.attention(w, seqs=seqs)
         c1 = time.perf_counter()
+        if f8 is not None:
+            # the timed call read the 8-bit cache: its reference is the merge of the exact attention over the shared
+            # levels and the exact attention over the decoded codes (the bf16 run above only times the oracle)
+            from oracle import fp8 as ofp8
+            Op, Lp = oracle.attention(w, suffix=False, seqs=seqs)
+            Os, Ls = ofp8.suffix_attention_fp8(w.Q[seqs], Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets[seqs],
+                                               w.lengths[seqs], w.scale)
+            Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
         cpu = {"value": len(seqs) / (c1 - c0), "unit": "queries/s per layer", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{len(seqs)} of {B} sequences (evenly spaced + shortest and longest suffix), all {Hq} heads, full key lists; "
                          f"{c1 - c0:.1f}s wall"}
@@ -268,7 +293,7 @@ def main() -> int:
         dL = float((np.abs(Lg - Lref) / np.abs(Lref)).max())
         rel = float(np.linalg.norm(Og - Oref) / np.linalg.norm(Oref))
         parity = {"max_abs_dO": dO, "max_rel_dLSE": dL, "rel_l2_O": rel, "max_abs_O": float(np.abs(Oref).max()), "sequences": len(seqs)}
-        if naive_ms is not None:
+        if naive_ms is not None and f8 is None:    # the comparison call read the bf16 cache
             Ogn = On[idx].float().cpu().numpy().astype(np.float64)
             parity["naive_max_abs_dO"] = float(np.abs(Ogn - Oref).max())
         ok = dO <= 1e-2 and dL <= 1e-3 and rel <= 1e-2
@@ -283,7 +308,7 @@ def main() -> int:
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
                    "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
                    "suffix_len": [int(w.lengths.min()), int(w.lengths.max())], "suffix_tokens": int(w.T), "seed": w.seed,
-                   "overlap_streams": args.overlap, "suffix_cache": f"paged, {args.paged} rows per page" if args.paged else "packed rows"},
+                   "overlap_streams": args.overlap, "suffix_cache": "packed rows, 8-bit E4M3 codes" if args.fp8_kv else f"paged, {args.paged} rows per page" if args.paged else "packed rows"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
