@@ -249,3 +249,42 @@ def test_fp8_error_paths():
     with pytest.raises(TypeError):
         hb.hg_suffix_attn_fp8(ctx, dw.Q, dw.Ks, dw.Vs, 1.0, 1.0, offs, dw.lengths, dw.max_len, O, L, dw.scale)   # bf16 cache
     ctx.close()
+
+
+def test_fp8_full_size_config3():
+    """The launch configuration `bench.py --fp8-kv` times (config 3, default options, bf16 output, 24 parts): sampled
+    sequences against the oracle, and properties that hold for every row."""
+    say("fp8 full config 3")
+    w = wl.config(3)
+    dw = dev.to_device(w)
+    f8 = wl.make_fp8(w, junk_code=None)
+    K8, V8, offs = u8(f8.Ks8), u8(f8.Vs8), i32(f8.offsets)
+    ctx = dev.make_context(dw, parts=24)
+    seqs = np.array(sorted({0, w.B - 1, w.B // 2, 333, int(np.argmin(w.lengths)), int(np.argmax(w.lengths))}), dtype=np.int32)
+    Op, Lp = oracle.attention(w, suffix=False, seqs=seqs)
+    Os, Ls = fp8.suffix_attention_fp8(w.Q[seqs], w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets[seqs],
+                                      w.lengths[seqs], w.scale)
+    Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
+    O = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.bfloat16, device="cuda:0")
+    L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
+    hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, K8, V8, f8.k_scale, f8.v_scale, offs, dw.lengths, dw.max_len, O, L, dw.scale)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(seqs.astype(np.int64)).cuda()
+    st = check(to_np(O[idx]), to_np(L[idx]), Oref, Lref, "fp8 full config 3", out_bf16=True)
+    say(f"   {st}")
+    assert bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(L).all())
+    # suffix part alone on every row: sampled rows against the oracle, and the full LSE dominates it everywhere
+    O2 = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.float32, device="cuda:0")
+    L2 = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
+    hb.hg_suffix_attn_fp8(ctx, dw.Q, K8, V8, f8.k_scale, f8.v_scale, offs, dw.lengths, dw.max_len, O2, L2, dw.scale)
+    torch.cuda.synchronize()
+    check(to_np(O2[idx]), to_np(L2[idx]), Os, Ls, "fp8 full config 3 suffix")
+    assert bool((L >= L2 - 1e-4).all())
+    # quantisation error against the bf16 cache stays at the format's level (3 mantissa bits: <= 2^-4 relative per
+    # element, averaged down by the softmax-weighted sum): a sanity bound, not a parity claim
+    Ob, _ = dev.hydragen(ctx, dw, torch.bfloat16)
+    torch.cuda.synchronize()
+    rel = float((Ob.float() - O.float()).norm() / Ob.float().norm())
+    say(f"   relative L2 difference to the bf16 cache: {rel:.4f}")
+    assert rel < 0.05
+    ctx.close()
