@@ -63,6 +63,7 @@ typedef struct hg_ctx hg_ctx;
 
 enum { HG_OK = 0, HG_ERR_INVALID_ARG = 1, HG_ERR_UNSUPPORTED = 2, HG_ERR_WORKSPACE = 3, HG_ERR_HIP = 4 };
 enum { HG_F32 = 0, HG_BF16 = 1 };
+enum { HG_KV_BF16 = 0, HG_KV_E4M3 = 1 }; /* element format of a paged suffix cache (hg_paged_kv.kv_format) */
 enum { HG_MAX_LEVELS = 4, HG_MAX_PARTS = 64 };
 
 /* Tunables for hg_set_option (0 = library default). */
@@ -173,6 +174,8 @@ int hg_hydragen_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* l
  * (so a bad table gives wrong numbers, never an access outside the pool).  page_size is a power of two in
  * [16, 1024]; table_stride >= ceil(max_len / page_size); n_pages * page_size * Hkv * D < 2^31.
  * Which page a sequence gets is the caller's business (a host-side allocator): the library only reads the table.
+ * kv_format = HG_KV_E4M3: the pool holds 8-bit E4M3 codes, one byte per element, with the scales k_scale / v_scale
+ * (see "8-bit suffix cache" below; the scales are ignored for HG_KV_BF16).  Zero-initialise the struct to get bf16.
  */
 typedef struct {
     void* K;
@@ -181,6 +184,9 @@ typedef struct {
     int page_size;
     int table_stride;
     int n_pages;
+    int kv_format;
+    float k_scale;
+    float v_scale;
 } hg_paged_kv;
 
 /*
@@ -226,6 +232,8 @@ int hg_kv_append_paged(hg_ctx* ctx, const void* Knew, const void* Vnew, const hg
  *   hg_kv_append_fp8: hg_kv_append with the new bf16 rows quantised on the way in:
  *     code = nearest E4M3 value to (x / scale) (fp32 quotient), ties to the even code, magnitudes above 448 -> 448.
  * Invalid scales (zero, negative, infinite, NaN) give HG_ERR_INVALID_ARG.
+ * A paged 8-bit cache goes through the paged calls above with hg_paged_kv.kv_format = HG_KV_E4M3
+ * (hg_suffix_attn_paged, hg_hydragen_attn_paged, hg_kv_append_paged: same meaning, rows addressed through the table).
  */
 int hg_suffix_attn_fp8(hg_ctx* ctx, const void* Q, const void* Ks8, const void* Vs8, float k_scale, float v_scale,
                        const int32_t* offsets, const int32_t* lengths, int max_len,

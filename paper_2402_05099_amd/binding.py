@@ -19,6 +19,7 @@ HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING, HG_OPT_PREFIX_KERNEL = 1, 2, 3, 4, 5, 6
 HG_OPT_WIDE_SLOTS = 7
 HG_OPT_NUM_QUERIES = 8
+HG_KV_BF16, HG_KV_E4M3 = 0, 1
 HG_OPT_SUFFIX_KERNEL = 9
 HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
@@ -53,6 +54,7 @@ class hg_paged_kv(ctypes.Structure):
     _fields_ = [
         ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
         ("page_size", ctypes.c_int), ("table_stride", ctypes.c_int), ("n_pages", ctypes.c_int),
+        ("kv_format", ctypes.c_int), ("k_scale", ctypes.c_float), ("v_scale", ctypes.c_float),
     ]
 
 
@@ -171,10 +173,13 @@ class Level:
 @dataclass
 class PagedKV:
     """A paged suffix cache on the device (see hg_paged_kv in include/hydragen.h)."""
-    K: torch.Tensor            # bf16 [n_pages * page_size, Hkv, D]
+    K: torch.Tensor            # bf16 (or uint8 E4M3 codes with kv_format = HG_KV_E4M3) [n_pages * page_size, Hkv, D]
     V: torch.Tensor
     page_table: torch.Tensor   # int32 [B, table_stride] on device
     page_size: int
+    kv_format: int = 0         # HG_KV_BF16 | HG_KV_E4M3
+    k_scale: float = 1.0
+    v_scale: float = 1.0
 
     @property
     def n_pages(self) -> int:
@@ -182,7 +187,7 @@ class PagedKV:
 
     def c_struct(self) -> hg_paged_kv:
         return hg_paged_kv(self.K.data_ptr(), self.V.data_ptr(), self.page_table.data_ptr(), self.page_size,
-                           int(self.page_table.shape[1]), self.n_pages)
+                           int(self.page_table.shape[1]), self.n_pages, self.kv_format, self.k_scale, self.v_scale)
 
 
 class Context:
@@ -325,7 +330,8 @@ def hg_naive_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths
 
 
 def _want_paged(kv: PagedKV, B: int, D: int) -> int:
-    _want(kv.K, torch.bfloat16, name="paged K"); _want(kv.V, torch.bfloat16, kv.K.shape, "paged V")
+    dt = torch.uint8 if kv.kv_format == HG_KV_E4M3 else torch.bfloat16
+    _want(kv.K, dt, name="paged K"); _want(kv.V, dt, kv.K.shape, "paged V")
     _want(kv.page_table, torch.int32, name="page_table")
     if kv.page_table.ndim != 2 or kv.page_table.shape[0] != B or kv.K.shape[2] != D or kv.K.shape[0] % kv.page_size:
         raise ValueError("paged cache: page_table must be [B, stride] and K [n_pages * page_size, Hkv, D]")

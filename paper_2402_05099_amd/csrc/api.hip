@@ -498,9 +498,24 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
 }
 
+// scales of an 8-bit cache: finite and positive
+static bool fp8_fmt(float k_scale, float v_scale, KvFmt* out) {
+    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3.0e38f || v_scale > 3.0e38f) return false;
+    out->fp8 = 1;
+    out->k_scale = k_scale;
+    out->v_scale = v_scale;
+    return true;
+}
+
 // checks an hg_paged_kv against the rows it must be able to address and translates it
-static int paged_dev(const hg_paged_kv* kv, int rows_per_seq, int Hkv, int D, hg::PagedDev* out) {
-    if (!kv || !out) return HG_ERR_INVALID_ARG;
+static int paged_dev(const hg_paged_kv* kv, int rows_per_seq, int Hkv, int D, hg::PagedDev* out, KvFmt* fmt) {
+    if (!kv || !out || !fmt) return HG_ERR_INVALID_ARG;
+    *fmt = KvFmt{};
+    if (kv->kv_format == HG_KV_E4M3) {
+        if (!fp8_fmt(kv->k_scale, kv->v_scale, fmt)) return HG_ERR_INVALID_ARG;
+    } else if (kv->kv_format != HG_KV_BF16) {
+        return HG_ERR_INVALID_ARG;
+    }
     int shift = 0;
     while ((1 << shift) < kv->page_size && shift < 11) ++shift;
     if (kv->page_size < 16 || kv->page_size > 1024 || (1 << shift) != kv->page_size) return HG_ERR_INVALID_ARG;
@@ -527,9 +542,10 @@ int hg_suffix_attn_paged(hg_ctx* c, const void* Q, const hg_paged_kv* kv, const 
                          int Hq, int Hkv, int D, float scale, void* O, int o_dtype, float* LSE) {
     if (max_len < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
     hg::PagedDev pg{};
-    const int rc = paged_dev(kv, max_len, Hkv, D, &pg);
+    KvFmt fmt;
+    const int rc = paged_dev(kv, max_len, Hkv, D, &pg, &fmt);
     if (rc) return rc;
-    return suffix_impl(c, Q, kv->K, kv->V, nullptr, lengths, max_len, B, Hq, Hkv, D, scale, O, o_dtype, LSE, pg, true);
+    return suffix_impl(c, Q, kv->K, kv->V, nullptr, lengths, max_len, B, Hq, Hkv, D, scale, O, o_dtype, LSE, pg, true, fmt);
 }
 
 int hg_merge(hg_ctx* c, int n, const void* const* O_parts, const float* const* LSE_parts, int o_dtype_in, int64_t rows,
@@ -732,11 +748,12 @@ int hg_hydragen_attn_paged(hg_ctx* c, const void* Q, int n_levels, const hg_leve
                            int o_dtype, float* LSE_out) {
     if (max_len < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
     hg::PagedDev pg{};
-    const int rc = paged_dev(kv, max_len, Hkv, D, &pg);
+    KvFmt fmt;
+    const int rc = paged_dev(kv, max_len, Hkv, D, &pg, &fmt);
     if (rc) return rc;
     if (max_len == 0) pg.table = nullptr;   // no suffix rows: the call reduces to the shared levels
     return fused_impl(c, Q, n_levels, levels, max_len > 0 ? kv->K : nullptr, kv->V, nullptr, lengths, max_len, B, Hq, Hkv, D,
-                      scale, O_out, o_dtype, LSE_out, pg);
+                      scale, O_out, o_dtype, LSE_out, pg, fmt);
 }
 
 // hg_kv_append and hg_kv_append_paged
@@ -777,19 +794,11 @@ int hg_kv_append_paged(hg_ctx* c, const void* Knew, const void* Vnew, const hg_p
                        int capacity, int B, int Hkv, int D) {
     if (capacity < 0 || Hkv <= 0 || (D != 64 && D != 128)) return HG_ERR_INVALID_ARG;
     hg::PagedDev pg{};
-    const int rc = paged_dev(kv, capacity, Hkv, D, &pg);
+    KvFmt fmt;
+    const int rc = paged_dev(kv, capacity, Hkv, D, &pg, &fmt);
     if (rc) return rc;
     if (capacity == 0) return HG_OK;
-    return append_impl(c, Knew, Vnew, kv->K, kv->V, nullptr, lengths, capacity, B, Hkv, D, pg);
-}
-
-// scales of an 8-bit cache: finite and positive
-static bool fp8_fmt(float k_scale, float v_scale, KvFmt* out) {
-    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3.0e38f || v_scale > 3.0e38f) return false;
-    out->fp8 = 1;
-    out->k_scale = k_scale;
-    out->v_scale = v_scale;
-    return true;
+    return append_impl(c, Knew, Vnew, kv->K, kv->V, nullptr, lengths, capacity, B, Hkv, D, pg, fmt);
 }
 
 int hg_suffix_attn_fp8(hg_ctx* c, const void* Q, const void* Ks8, const void* Vs8, float k_scale, float v_scale,

@@ -4,7 +4,7 @@
 // kernels do: every sequence re-reads the shared rows).  Memory-bound: one wavefront per work item
 // (sequence, KV head, group of GT query heads, key chunk), 16-byte bf16 loads, fp32 arithmetic on the
 // vector ALU, DPP reductions inside the 16-lane row that holds one key.
-// FP8 = true (suffix rows only, packed): the cache holds 8-bit E4M3 codes with one fp32 scale per tensor (not in the
+// FP8 = true (suffix rows only, packed or paged): the cache holds 8-bit E4M3 codes with one fp32 scale per tensor (not in the
 // paper: half the bytes for the part of the method that is bound by them).  The same lanes own the same 8 columns,
 // fetched with 8-byte loads and converted two at a time by the hardware; the K scale is folded into the query, the
 // V scale into the final normalisation.
@@ -196,7 +196,7 @@ __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16
 // wavefront holds the physical page of the span's i-th logical page; the 4 or 8 keys of one wave-wide load never
 // straddle a page (pages hold at least 16 rows), so the page of a load is wavefront-uniform: one v_readlane and
 // a few scalar instructions per load, the same unpredicated vector loads and the same pipeline as above.
-template <int D, int GT>
+template <int D, int GT, bool FP8 = false>
 __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
                                                   const uint16_t* __restrict__ V, const PagedDev& pg, int b, int start,
                                                   int n, int Hkv, int kvh, int lane) {
@@ -204,12 +204,13 @@ __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const 
     constexpr int KPW = 64 / LPR;
     constexpr int U = GT >= 8 ? 2 : 4;
     constexpr int STEP = KPW * U;
+    constexpr unsigned ES = FP8 ? 1u : 2u;     // bytes per element
     const int sub = lane / LPR;
-    const unsigned rstride_b = (unsigned)Hkv * D * 2u;
-    const unsigned colb = (unsigned)(lane % LPR) * 16u;
+    const unsigned rstride_b = (unsigned)Hkv * D * ES;
+    const unsigned colb = (unsigned)(lane % LPR) * 8u * ES;
     const unsigned subrow = (unsigned)sub * rstride_b + colb;
-    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K + (int64_t)kvh * D));
-    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V + (int64_t)kvh * D));
+    const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K) + (int64_t)kvh * D * ES);
+    const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V) + (int64_t)kvh * D * ES);
     const int shift = pg.shift;
     const int lp0 = start >> shift;
     const int lpn = ((start + n - 1) >> shift) - lp0 + 1;
@@ -223,26 +224,26 @@ __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const 
         return ((unsigned)(page << shift) + (unsigned)(pos & ((1 << shift) - 1))) * rstride_b;
     };
     const unsigned safe = row_base(0) + colb;   // lanes past the span read its first row (their scores are masked)
-    auto load = [&](KVBatch<D, U, false>& bt, int i0) {
+    auto load = [&](KVBatch<D, U, FP8>& bt, int i0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int iu = i0 + u * KPW;
             const unsigned off = iu + sub < n ? row_base(iu) + subrow : safe;
-            bt.k[u] = ldg128<true>(kb, off);
-            bt.v[u] = ldg128<true>(vb, off);
+            bt.k[u] = ldg_row<true, FP8>(kb, off);
+            bt.v[u] = ldg_row<true, FP8>(vb, off);
         }
     };
 
-    KVBatch<D, U, false> ba, bb;
+    KVBatch<D, U, FP8> ba, bb;
     load(ba, 0);
     for (int it = 0; it < n; it += 2 * STEP) {
         load(bb, it + STEP);
         __builtin_amdgcn_sched_barrier(0);
-        consume_batch<D, GT, U, false>(st, ba, it + sub, n);
+        consume_batch<D, GT, U, FP8>(st, ba, it + sub, n);
         __builtin_amdgcn_sched_barrier(0);
         load(ba, it + 2 * STEP);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + STEP < n) consume_batch<D, GT, U, false>(st, bb, it + STEP + sub, n);
+        if (it + STEP < n) consume_batch<D, GT, U, FP8>(st, bb, it + STEP + sub, n);
     }
 }
 
@@ -271,7 +272,7 @@ __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& 
 // SHARED = false: suffix rows only (the Hydragen suffix part).  SHARED = true: the shared blocks of every level
 // are walked too (the non-decomposed comparison); a separate instantiation so that profiles tell them apart.
 // PAGED (only without SHARED): the suffix rows are read through a page table.
-// FP8 (only without SHARED and PAGED): the suffix rows are E4M3 codes; a key is code * a.k_scale, a value code * a.v_scale.
+// FP8 (only without SHARED): the suffix rows are E4M3 codes; a key is code * a.k_scale, a value code * a.v_scale.
 template <int D, int GT, bool SHARED, bool PAGED, bool FP8 = false>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     constexpr int LPR = D / 8;
@@ -322,7 +323,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         if (count < 0) count = 0;
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
         if (s0 < s1) {
-            if constexpr (PAGED) decode_span_paged<D, GT>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
+            if constexpr (PAGED) decode_span_paged<D, GT, FP8>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
             else decode_span<D, GT, true, FP8>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
         }
     }
@@ -371,8 +372,9 @@ static hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     const int64_t grid = (a.units + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.fp8) {
-        if (a.n_levels > 0 || a.pg.table) return hipErrorInvalidValue;   // 8-bit rows: packed suffix only
-        decode_kernel<D, GT, false, false, true><<<(unsigned)grid, 256, 0, s>>>(a);
+        if (a.n_levels > 0) return hipErrorInvalidValue;   // 8-bit rows: suffix only
+        if (a.pg.table) decode_kernel<D, GT, false, true, true><<<(unsigned)grid, 256, 0, s>>>(a);
+        else decode_kernel<D, GT, false, false, true><<<(unsigned)grid, 256, 0, s>>>(a);
     } else if (a.pg.table) {
         if (a.n_levels > 0) return hipErrorInvalidValue;   // the comparison kernel has no paged form
         decode_kernel<D, GT, false, true><<<(unsigned)grid, 256, 0, s>>>(a);

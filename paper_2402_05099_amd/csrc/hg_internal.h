@@ -87,7 +87,7 @@ struct DecodeArgs {
     int seg;          // matrix-core kernel: 1 = the keys of sequence b are the rows of the block of lv[0] that covers b
                       // (Ks/Vs then point at that level's tensors; offsets/lengths are unused, no causal bound)
     float scale;
-    int fp8;          // vector-ALU kernel, packed suffix only: Ks/Vs hold E4M3 codes (one byte per element)
+    int fp8;          // vector-ALU kernel, suffix only: Ks/Vs hold E4M3 codes (one byte per element)
     float k_scale, v_scale;   // value = code * scale (fp8 only)
     OutDev out;       // part index = chunk
 };
@@ -113,7 +113,7 @@ struct AppendArgs {
     int capacity;             // rows reserved per sequence
     int B, nq;
     int row_elems;            // Hkv * D
-    int fp8;                  // the cache holds E4M3 codes: code = nearest(value / scale), saturating (packed rows only)
+    int fp8;                  // the cache holds E4M3 codes: code = nearest(value / scale), saturating
     float k_scale, v_scale;
 };
 

@@ -50,7 +50,7 @@ __device__ __forceinline__ uint2 quantize8(const uint4& r, float scale) {
     return make_uint2((unsigned)lo, (unsigned)hi);
 }
 
-// The same update for a cache of E4M3 codes (packed rows): the new bf16 rows are quantised on the way in.
+// The same update for a cache of E4M3 codes: the new bf16 rows are quantised on the way in.
 __global__ __launch_bounds__(256) void kv_append_fp8_kernel(AppendArgs a) {
     const int b = blockIdx.x;
     const int len = a.lengths[b];
@@ -60,7 +60,15 @@ __global__ __launch_bounds__(256) void kv_append_fp8_kernel(AppendArgs a) {
     const int vec = a.row_elems / 8;       // 8-element groups per row: 16 bytes in, 8 bytes out
     for (int i = threadIdx.x; i < take * vec; i += 256) {
         const int t = i / vec, c = i - t * vec;
-        const int64_t row = (int64_t)a.offsets[b] + len + t;
+        const int j = len + t;
+        int64_t row;
+        if (a.pg.table) {
+            int page = a.pg.table[(int64_t)b * a.pg.stride + (j >> a.pg.shift)];
+            page = min(max(page, 0), a.pg.n_pages - 1);
+            row = ((int64_t)page << a.pg.shift) + (j & ((1 << a.pg.shift) - 1));
+        } else {
+            row = (int64_t)a.offsets[b] + j;
+        }
         const int64_t src = ((int64_t)b * a.nq + t) * vec + c;
         const int64_t dst = row * vec + c;
         reinterpret_cast<uint2*>(a.Ks)[dst] = quantize8(reinterpret_cast<const uint4*>(a.Knew)[src], a.k_scale);
@@ -72,7 +80,6 @@ __global__ __launch_bounds__(256) void kv_append_fp8_kernel(AppendArgs a) {
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s) {
     if (a.B == 0) return hipSuccess;
     if (a.fp8) {
-        if (a.pg.table) return hipErrorInvalidValue;
         kv_append_fp8_kernel<<<(unsigned)a.B, 256, 0, s>>>(a);
     } else {
         kv_append_kernel<<<(unsigned)a.B, 256, 0, s>>>(a);

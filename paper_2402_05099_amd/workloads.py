@@ -372,3 +372,28 @@ def make_fp8(w: Workload, reserve: int = 0, headroom: float = 1.0, junk_code: Op
         out.append(full)
         scales.append(scale)
     return Fp8Suffix(Ks8=out[0], Vs8=out[1], k_scale=scales[0], v_scale=scales[1], offsets=offsets, capacity=cap)
+
+
+def make_paged_fp8(w: Workload, page_size: int, reserve: int = 0, spare_pages: int = 3, headroom: float = 1.0):
+    """(PagedSuffix with uint8 pools, k_scale, v_scale): make_fp8's codes scattered into pages as make_paged does.
+
+    Rows no sequence owns (page tails, reserved rows, spare pages) hold the NaN code 0x7f.
+    """
+    f8 = make_fp8(w, headroom=headroom, junk_code=None)
+    ps = int(page_size)
+    cap = w.max_len + reserve
+    per_seq = (cap + ps - 1) // ps
+    n_pages = w.B * per_seq + spare_pages
+    rng = np.random.default_rng(np.random.SeedSequence([w.seed, 115, ps]))
+    phys = rng.permutation(n_pages).astype(np.int32)[: w.B * per_seq].reshape(w.B, per_seq) if w.B else np.zeros((0, per_seq), np.int32)
+    table = np.full((w.B, per_seq + 1), -1, dtype=np.int32)
+    table[:, :per_seq] = phys
+    K = np.full((n_pages * ps, w.Hkv, w.D), 0x7F, dtype=np.uint8)
+    V = np.full((n_pages * ps, w.Hkv, w.D), 0x7F, dtype=np.uint8)
+    for b in range(w.B):
+        n = int(w.lengths[b])
+        j = np.arange(n)
+        rows = phys[b, j // ps].astype(np.int64) * ps + j % ps
+        K[rows] = f8.Ks8[f8.offsets[b]: f8.offsets[b] + n]
+        V[rows] = f8.Vs8[f8.offsets[b]: f8.offsets[b] + n]
+    return PagedSuffix(K=K, V=V, table=table, page_size=ps, capacity=cap), f8.k_scale, f8.v_scale

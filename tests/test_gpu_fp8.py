@@ -288,3 +288,94 @@ def test_fp8_full_size_config3():
     say(f"   relative L2 difference to the bf16 cache: {rel:.4f}")
     assert rel < 0.05
     ctx.close()
+
+
+def paged_fp8_to_device(pg, k_scale, v_scale) -> hb.PagedKV:
+    return hb.PagedKV(K=u8(pg.K), V=u8(pg.V), page_table=i32(pg.table), page_size=pg.page_size, kv_format=hb.HG_KV_E4M3,
+                      k_scale=k_scale, v_scale=v_scale)
+
+
+@pytest.mark.parametrize("page_size", [16, 128])
+@pytest.mark.parametrize("case", ["mha", "ragged", "gqa8", "tree", "ragged_nq3"])
+def test_paged_fp8_suffix_and_fused(case, page_size):
+    """The 8-bit cache through a page table: the oracle gathers the rows the table designates (byte work), then takes the
+    exact attention of the decoded codes; unowned pool rows hold a NaN code."""
+    say(f"fp8 paged {case} page_size={page_size}")
+    kw = dict(CASES[case])
+    w = wl.scaled_down(kw.pop("idx"), **kw)
+    dw = dev.to_device(w)
+    pg, ks, vs = wl.make_paged_fp8(w, page_size)
+    kv = paged_fp8_to_device(pg, ks, vs)
+    K8, V8, offs = oracle.paged_to_packed(pg.K, pg.V, pg.table, pg.page_size, w.lengths)
+    Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, K8, V8, ks, vs, offs, w.lengths, w.scale)
+    ctx = dev.make_context(dw, parts=24)
+    O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
+    L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+    hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
+    torch.cuda.synchronize()
+    check(to_np(O), to_np(L), Os, Ls, f"fp8 paged suffix {case}")
+    # same codes in packed rows, same kernel, same order of operations: identical bits
+    f8 = wl.make_fp8(w, junk_code=None)
+    O2, L2 = torch.empty_like(O), torch.empty_like(L)
+    hb.hg_suffix_attn_fp8(ctx, dw.Q, u8(f8.Ks8), u8(f8.Vs8), ks, vs, i32(f8.offsets), dw.lengths, dw.max_len, O2, L2, dw.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2) and torch.equal(L, L2)
+    Op, Lp = oracle.attention(w, suffix=False)
+    Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
+    Of, Lf = dev.hydragen_paged(ctx, dw, kv, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check(to_np(Of), to_np(Lf), Oref, Lref, f"fp8 paged fused {case}")
+    ctx.close()
+
+
+def test_paged_fp8_append_then_attend():
+    say("fp8 paged append")
+    w = wl.scaled_down(3, nq=2)
+    dw = dev.to_device(w)
+    pg, ks, vs = wl.make_paged_fp8(w, 32, reserve=4)
+    kv = paged_fp8_to_device(pg, ks, vs)
+    Ld = i32(w.lengths)
+    Kh, Vh, Lh = pg.K, pg.V, w.lengths.copy()
+    ctx = dev.make_context(dw, parts=24)
+    for step in range(2):
+        Knew, Vnew = wl.new_rows(w, step)
+        hb.hg_kv_append_paged(ctx, dev.bf16_tensor(Knew, "cuda:0"), dev.bf16_tensor(Vnew, "cuda:0"), kv, Ld, pg.capacity)
+        torch.cuda.synchronize()
+        Kh, Vh, Lh = oracle.kv_append_paged(Kh, Vh, pg.table, pg.page_size, Lh, pg.capacity,
+                                            fp8.quantize(wl.bf16_bits_to_f32(Knew), ks), fp8.quantize(wl.bf16_bits_to_f32(Vnew), vs))
+        assert np.array_equal(Ld.cpu().numpy(), Lh)
+        assert np.array_equal(kv.K.cpu().numpy(), Kh) and np.array_equal(kv.V.cpu().numpy(), Vh)
+        K8, V8, offs = oracle.paged_to_packed(Kh, Vh, pg.table, pg.page_size, Lh)
+        Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, K8, V8, ks, vs, offs, Lh, w.scale)
+        O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+        L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+        hb.hg_suffix_attn_paged(ctx, dw.Q, kv, Ld, pg.capacity, O, L, dw.scale)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), Os, Ls, f"fp8 paged append step {step}")
+    ctx.close()
+
+
+def test_paged_fp8_error_paths():
+    say("fp8 paged errors")
+    w = wl.scaled_down(1)
+    dw = dev.to_device(w)
+    pg, ks, vs = wl.make_paged_fp8(w, 16)
+    ctx = dev.make_context(dw, parts=4)
+    O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+    L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+    for bad in (dict(k_scale=0.0), dict(v_scale=float("nan"))):
+        kv = paged_fp8_to_device(pg, ks, vs)
+        for k, v in bad.items():
+            setattr(kv, k, v)
+        with pytest.raises(hb.HydragenError) as e:
+            hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert e.value.code == hb.HG_ERR_INVALID_ARG
+    # an unknown format code, straight through the C ABI (the binding would object to the tensor type first)
+    import ctypes
+    kv = paged_fp8_to_device(pg, ks, vs)
+    st = kv.c_struct()
+    st.kv_format = 7
+    rc = hb.lib().hg_suffix_attn_paged(ctx.h, dw.Q.data_ptr(), ctypes.byref(st), dw.lengths.data_ptr(), dw.max_len, dw.B, dw.Hq,
+                                       dw.Hkv, dw.D, dw.scale, O.data_ptr(), hb.HG_F32, L.data_ptr())
+    assert rc == hb.HG_ERR_INVALID_ARG
+    ctx.close()
