@@ -183,8 +183,8 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
-    // an 8-bit cache is read by the vector-ALU kernel only
-    p.mfma = !fp8 && D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
+    (void)fp8;   // both kernels read either cache format
+    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);

@@ -17,6 +17,12 @@
 //
 // Several queries per sequence: row r of a sequence's R rows is (query t, head g) = (r / G, r % G); query t sees
 // suffix rows [0, length - (nq-1-t)), applied as a per-lane bound on the key index in the stages that reach it.
+//
+// FP8: the suffix rows are 8-bit E4M3 codes (one fp32 scale per tensor; not in the paper).  A K/V ring element is then
+// 4 KiB + 4 KiB of codes (half the copy instructions); before a stage is multiplied the wavefront expands it into one
+// bf16 work stage in LDS with the layout the bf16 path reads (v_cvt_scalef32_pk_bf16_fp8, exact: every E4M3 value
+// is a bf16 value), so the products and the softmax are the same code.  The K scale multiplies the softmax scale,
+// the V scale the final normalisation.
 #include "hg_internal.h"
 #include "prefix_common.h"
 
@@ -61,11 +67,20 @@ __device__ __forceinline__ void wait_vm() {
 // lie in one page (pages hold a power of two >= 16 rows), so a copy still has one scalar base.
 // SEG: the key range of sequence b is the block of level a.lv[0] that covers b (the non-decomposed comparison walks
 // the shared blocks per sequence); every query of the sequence sees all of it.
-template <int NS, bool PAGED, bool SEG>
+template <int NS, bool PAGED, bool SEG, bool FP8 = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
-    constexpr int VRING = NS * STB;
-    constexpr int QOPS = CPS, KVOPS = 2 * CPS;     // copy instructions per ring element
+    static_assert(!(FP8 && SEG), "shared levels are bf16");
+    // bf16: ring slot n holds K (or Q) at n * STB and V at VRING + n * STB.  FP8: ring slot n holds the K codes at
+    // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot); the bf16 work stage that the products
+    // read is K at NS * STB and V at (NS + 1) * STB.  Either way 2 * NS * STB bytes when NS = 2.
+    constexpr int VRING = FP8 ? STB : NS * STB;    // from the K stage the products read to its V stage
+    constexpr int ES = FP8 ? 1 : 2;                // bytes per cache element
+    constexpr int CPRG = D * ES / 16;              // 16-byte chunks per cache row
+    constexpr int RPIG = 64 / CPRG;                // cache rows one copy instruction covers
+    constexpr int CPSG = KT / RPIG;                // copy instructions per stage and tensor
+    constexpr int QOPS = CPS, KVOPS = 2 * CPSG;    // copy instructions per ring element
+    constexpr int VSLOT = FP8 ? STB / 2 : NS * STB;   // from a ring element's K part to its V part
     unsigned char* const smem = dm_smem;
     const int l = threadIdx.x, lq = l & 31, hl = l >> 5;
     const int R = a.nq * a.G;
@@ -153,8 +168,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     // last stage re-reads the 32 rows that end the range (rows before ks belong to an earlier chunk or sequence and
     // are masked), so every copy has the same shape; row i of a stage is a key of it iff ks + 32 t <= k0c + i < ke.
     // 16-byte chunks are XOR-swizzled on the global side (K and Q: chunk ^ row % 16, V: chunk ^ 4 (row % 4)).
-    const unsigned rstride_b = (unsigned)a.Hkv * D * 2u;
+    const unsigned rstride_b = (unsigned)a.Hkv * D * ES;
     const int lrow = l / CPR, sch = l % CPR;
+    const int lrowg = l / CPRG, schg = l % CPRG;   // cache row within a copy instruction and 16-byte chunk of this lane
     const unsigned ldsb = (unsigned)(uintptr_t)HG_LDS(smem);
     // Base pointers and LDS addresses are wavefront-uniform; readfirstlane puts them in scalar registers even where
     // the compiler computed them with vector instructions (64-bit multiplies).  Done once per ring element: a copy
@@ -209,11 +225,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         if (rowclamp != voff_clamp) {
             voff_clamp = rowclamp;
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) {
-                const int srow = i * RPI + lrow;
+            for (int i = 0; i < CPSG; ++i) {
+                const int srow = i * RPIG + lrowg;
                 const unsigned ro = (unsigned)min(srow, rowclamp) * rstride_b;
-                voffK[i] = ro + (unsigned)((sch ^ (srow % CPR)) * 16);
-                voffV[i] = ro + (unsigned)((sch ^ (4 * (srow % 4))) * 16);
+                if (FP8) {
+                    // codes land in copy order (lane l of copy i holds row 8i + l/8, bytes 16 (l%8) ..): the expansion
+                    // reads them back the same way and applies the swizzles when it writes the bf16 stage
+                    voffK[i] = voffV[i] = ro + (unsigned)(schg * 16);
+                } else {
+                    voffK[i] = ro + (unsigned)((sch ^ (srow % CPR)) * 16);
+                    voffV[i] = ro + (unsigned)((sch ^ (4 * (srow % 4))) * 16);
+                }
             }
         }
         if (pit.rt != voff_rt) {
@@ -248,27 +270,27 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             const int pg0 = min(max(table_c[trow + e0], 0), a.pg.n_pages - 1);   // pages of rows r0.. and r0+16..
             const int pg1 = min(max(table_c[trow + e1], 0), a.pg.n_pages - 1);
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) {
-                const int jr = r0 + i * RPI;
-                const int page = i < CPS / 2 ? pg0 : pg1;
+            for (int i = 0; i < CPSG; ++i) {
+                const int jr = r0 + i * RPIG;
+                const int page = i < CPSG / 2 ? pg0 : pg1;
                 const int64_t prow = ((int64_t)page << shift) + (jr & ps_mask);
-                const int64_t goff = prow * rstride_b + (int64_t)pit.kvh * ROWB;
+                const int64_t goff = prow * rstride_b + (int64_t)pit.kvh * (D * ES);
                 const unsigned char* const kg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Ks) + goff);
                 const unsigned char* const vg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Vs) + goff);
-                const unsigned back = (unsigned)(i * RPI) * rstride_b;    // voffK/V count rows from the stage's first row
-                copy16(kg, voffK[i] - back, dst + i * (RPI * ROWB));
-                copy16(vg, voffV[i] - back, dst + VRING + i * (RPI * ROWB));
+                const unsigned back = (unsigned)(i * RPIG) * rstride_b;    // voffK/V count rows from the stage's first row
+                copy16(kg, voffK[i] - back, dst + i * 1024);
+                copy16(vg, voffV[i] - back, dst + VSLOT + i * 1024);
             }
             pending += KVOPS;
         } else {
             const int k0c = min(pit.ks + p_el * KT, pit.kwin);
-            const int64_t goff = (int64_t)k0c * rstride_b + (int64_t)pit.kvh * ROWB;
+            const int64_t goff = (int64_t)k0c * rstride_b + (int64_t)pit.kvh * (D * ES);
             const unsigned char* const kg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Ks) + goff);
             const unsigned char* const vg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Vs) + goff);
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) copy16(kg, voffK[i], dst + i * (RPI * ROWB));
+            for (int i = 0; i < CPSG; ++i) copy16(kg, voffK[i], dst + i * 1024);
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) copy16(vg, voffV[i], dst + VRING + i * (RPI * ROWB));
+            for (int i = 0; i < CPSG; ++i) copy16(vg, voffV[i], dst + VSLOT + i * 1024);
             pending += KVOPS;
         }
         ++n_issued;
@@ -297,7 +319,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     for (int s = 0; s < NS - 1; ++s) produce_one();
 
     // ---- consumer ---------------------------------------------------------------------------------------------------------
-    const float c2 = a.scale * kLog2e;
+    const float kscale = FP8 ? a.scale * a.k_scale : a.scale;   // raw scores are in units of the codes
+    const float c2 = kscale * kLog2e;
     const float tau_raw = TAU / c2;
     int c_item = item0, c_el = -1, n_done = 0;
     Item cit{};
@@ -385,13 +408,37 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         } else {
             pending -= KVOPS;
             wait_for(pending);
+            if constexpr (FP8) {
+                // expand the codes of this element into the bf16 work stage: lane l of copy i holds row 8i + l/8,
+                // columns 16 (l%8) .. +15, i.e. the two 16-byte chunks 2 (l%8) and 2 (l%8) + 1 of the bf16 row
+                unsigned char* const wk = smem + NS * STB;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                    for (int i = 0; i < CPSG; ++i) {
+                        const uintx4 raw = *reinterpret_cast<const uintx4*>(sb + t * VSLOT + i * 1024 + l * 16);
+                        unsigned w[8];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            w[2 * j] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, false));
+                            w[2 * j + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
+                        }
+                        const int row = i * RPIG + lrowg;
+                        const int swz = t == 0 ? row % CPR : 4 * (row % 4);
+                        unsigned char* const rowp = wk + t * VRING + row * ROWB;
+                        *reinterpret_cast<uintx4*>(rowp + (((2 * schg) ^ swz) * 16)) = uintx4{w[0], w[1], w[2], w[3]};
+                        *reinterpret_cast<uintx4*>(rowp + (((2 * schg + 1) ^ swz) * 16)) = uintx4{w[4], w[5], w[6], w[7]};
+                    }
+                }
+            }
+            const unsigned char* const fb = FP8 ? smem + NS * STB : sb;    // the bf16 stage the products read
             // S^T = K Q^T
             floatx16 S;
 #pragma unroll
             for (int i = 0; i < 16; ++i) S[i] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const uintx4 kv = *reinterpret_cast<const uintx4*>(sb + kaddr[s]);
+                const uintx4 kv = *reinterpret_cast<const uintx4*>(fb + kaddr[s]);
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S, 0, 0, 0);
             }
             // keys outside [key0, min(ke, vis_end)): stage rows before the stage's first key (window clamp), rows past
@@ -410,7 +457,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // the rows past the range are a page's unwritten tail (or another page altogether): clear their V rows
                 // in LDS, since their zero probabilities would still turn a NaN into a NaN in the second product
                 const int nhi = cit.ke - key0;
-                unsigned char* const vs = smem + (sb - smem) + VRING;
+                unsigned char* const vs = smem + (fb - smem) + VRING;
 #pragma unroll
                 for (int i = 0; i < CPS; ++i) {
                     const int row = i * RPI + lrow;
@@ -422,7 +469,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // sequence's slot of the cache, possibly padding that was never written.  Their probabilities are
                 // zero, but 0 * NaN is NaN in the second product: clear those V rows in LDS.
                 const int nlo = key0 - k0c;
-                unsigned char* const vs = smem + (sb - smem) + VRING;
+                unsigned char* const vs = smem + (fb - smem) + VRING;
 #pragma unroll
                 for (int i = 0; i < CPS; ++i) {
                     const int row = i * RPI + lrow;
@@ -462,7 +509,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const unsigned char* vp = sb + vaddr[db] + tt * 16 * ROWB;
+                    const unsigned char* vp = fb + vaddr[db] + tt * 16 * ROWB;
                     const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
                     const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
                     const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -481,7 +528,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             if (rv) {
                 float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
                 uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
-                const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;    // a row that sees no key of this chunk: O = 0, LSE = -inf
+                const float inv = ltot > 0.f ? (FP8 ? a.v_scale / ltot : 1.0f / ltot) : 0.f;    // a row that sees no key of this chunk: O = 0, LSE = -inf
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -493,7 +540,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                         else *reinterpret_cast<float4*>(Of + d) = make_float4(o0, o1, o2, o3);
                     }
                 }
-                if (hl == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = ltot > 0.f ? m_used * a.scale + __logf(ltot) : -INFINITY;
+                if (hl == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = ltot > 0.f ? m_used * kscale + __logf(ltot) : -INFINITY;
             }
             c_el = -1;
             ++c_item;
@@ -509,8 +556,12 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
     if (a.items == 0) return hipSuccess;
     if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
     const int grid = (a.items + a.ipw - 1) / a.ipw;
-    if (a.pg.table) {
-        if (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1) return hipErrorInvalidValue;
+    if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
+    if (a.fp8) {
+        if (a.seg) return hipErrorInvalidValue;
+        if (a.pg.table) decode_mfma_kernel<NS, true, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        else decode_mfma_kernel<NS, false, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+    } else if (a.pg.table) {
         decode_mfma_kernel<NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else if (a.seg) {
         decode_mfma_kernel<NS, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);

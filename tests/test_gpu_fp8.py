@@ -35,28 +35,39 @@ def finite_codes(n_rows: int) -> np.ndarray:
     return np.broadcast_to(row.reshape(1, 2, 128), (n_rows, 2, 128)).copy()
 
 
-def test_every_value_code_is_decoded_exactly():
+KERNELS = pytest.mark.parametrize("kernel", [1, 2], ids=["valu", "mfma"])
+
+
+@KERNELS
+def test_every_value_code_is_decoded_exactly(kernel):
     """One key per sequence, so the softmax weight is exactly 1 and O = decode(V code) * v_scale, one fp32 product."""
-    say("fp8 decode of every V code")
+    say(f"fp8 decode of every V code, kernel {kernel}")
     B, H, D = 3, 2, 128
     Vs8 = finite_codes(B)
     Ks8 = np.full((B, H, D), 0x38, dtype=np.uint8)
     Q = dev.bf16_tensor(wl.normal_bf16(1, 0, (B, H, D)), "cuda:0")
     offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
     ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
     O = torch.full((B, H, D), float("nan"), dtype=torch.float32, device="cuda:0")
     L = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda:0")
     v_scale = 0.37
     hb.hg_suffix_attn_fp8(ctx, Q, u8(Ks8), u8(Vs8), 0.5, v_scale, offsets, lengths, 1, O, L)
     torch.cuda.synchronize()
     want = fp8.e4m3_decode(Vs8).astype(np.float32) * np.float32(v_scale)
-    assert np.array_equal(O.cpu().numpy(), want)
+    if kernel == 1:
+        assert np.array_equal(O.cpu().numpy(), want)
+    else:
+        # the matrix-core kernel takes exp2(s c - round(m c)): the single weight is 1 up to a few ulps, and cancels
+        # only up to that in O = p v / p.  Neighbouring codes differ by 6 % or more.
+        assert np.allclose(O.cpu().numpy(), want, rtol=1e-5, atol=0.0)
     ctx.close()
 
 
-def test_every_key_code_is_decoded_exactly():
+@KERNELS
+def test_every_key_code_is_decoded_exactly(kernel):
     """One key per sequence and a one-hot query: LSE is the single score q_d * decode(K code) * k_scale * scale."""
-    say("fp8 decode of every K code")
+    say(f"fp8 decode of every K code, kernel {kernel}")
     B, H, D = 128, 2, 128
     Ks8 = finite_codes(B)
     Vs8 = np.full((B, H, D), 0x38, dtype=np.uint8)
@@ -66,6 +77,7 @@ def test_every_key_code_is_decoded_exactly():
     Q = dev.bf16_tensor(wl.f32_to_bf16_bits(q), "cuda:0")
     offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
     ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
     O = torch.empty((B, H, D), dtype=torch.float32, device="cuda:0")
     L = torch.empty((B, H), dtype=torch.float32, device="cuda:0")
     k_scale, scale = 0.75, 0.25
@@ -75,7 +87,7 @@ def test_every_key_code_is_decoded_exactly():
     want = 2.0 * vals.T * k_scale * scale                           # [B = d, H]
     got = L.cpu().numpy().astype(np.float64)
     assert np.allclose(got, want, rtol=2e-6, atol=1e-9), float(np.abs(got - want).max())
-    assert np.array_equal(O.cpu().numpy(), np.ones((B, H, D), dtype=np.float32))
+    assert np.allclose(O.cpu().numpy(), np.ones((B, H, D), dtype=np.float32), rtol=1e-5 if kernel == 2 else 0.0, atol=0.0)
     ctx.close()
 
 
@@ -90,16 +102,18 @@ CASES = {
 }
 
 
+@KERNELS
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("chunk", [0, 64], ids=["auto", "chunk64"])
 @pytest.mark.parametrize("case", sorted(CASES))
-def test_suffix_attn_fp8(case, chunk, out_dtype):
-    say(f"fp8 suffix {case} chunk={chunk} {out_dtype}")
+def test_suffix_attn_fp8(case, chunk, out_dtype, kernel):
+    say(f"fp8 suffix {case} chunk={chunk} {out_dtype} kernel={kernel}")
     kw = dict(CASES[case])
     w = wl.scaled_down(kw.pop("idx"), **kw)
     dw = dev.to_device(w)
     f8 = wl.make_fp8(w, reserve=5)                  # unowned rows hold a NaN code
     ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)  # 2: the matrix-core kernel wherever D = 128 (D = 64 stays on the vector ALU)
     if chunk:
         ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
     Oref, Lref = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
@@ -295,12 +309,13 @@ def paged_fp8_to_device(pg, k_scale, v_scale) -> hb.PagedKV:
                       k_scale=k_scale, v_scale=v_scale)
 
 
+@KERNELS
 @pytest.mark.parametrize("page_size", [16, 128])
 @pytest.mark.parametrize("case", ["mha", "ragged", "gqa8", "tree", "ragged_nq3"])
-def test_paged_fp8_suffix_and_fused(case, page_size):
+def test_paged_fp8_suffix_and_fused(case, page_size, kernel):
     """The 8-bit cache through a page table: the oracle gathers the rows the table designates (byte work), then takes the
     exact attention of the decoded codes; unowned pool rows hold a NaN code."""
-    say(f"fp8 paged {case} page_size={page_size}")
+    say(f"fp8 paged {case} page_size={page_size} kernel={kernel}")
     kw = dict(CASES[case])
     w = wl.scaled_down(kw.pop("idx"), **kw)
     dw = dev.to_device(w)
@@ -309,17 +324,22 @@ def test_paged_fp8_suffix_and_fused(case, page_size):
     K8, V8, offs = oracle.paged_to_packed(pg.K, pg.V, pg.table, pg.page_size, w.lengths)
     Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, K8, V8, ks, vs, offs, w.lengths, w.scale)
     ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
     O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
     L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
     hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
     torch.cuda.synchronize()
     check(to_np(O), to_np(L), Os, Ls, f"fp8 paged suffix {case}")
-    # same codes in packed rows, same kernel, same order of operations: identical bits
+    # same codes in packed rows: the vector-ALU kernel walks them in the same order, identical bits (the matrix-core
+    # kernel aligns its stages to logical rows when paged and to the range's end when packed: parity only)
     f8 = wl.make_fp8(w, junk_code=None)
     O2, L2 = torch.empty_like(O), torch.empty_like(L)
     hb.hg_suffix_attn_fp8(ctx, dw.Q, u8(f8.Ks8), u8(f8.Vs8), ks, vs, i32(f8.offsets), dw.lengths, dw.max_len, O2, L2, dw.scale)
     torch.cuda.synchronize()
-    assert torch.equal(O, O2) and torch.equal(L, L2)
+    if kernel == 1:
+        assert torch.equal(O, O2) and torch.equal(L, L2)
+    else:
+        check(to_np(O2), to_np(L2), Os, Ls, f"fp8 packed suffix {case}")
     Op, Lp = oracle.attention(w, suffix=False)
     Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
     Of, Lf = dev.hydragen_paged(ctx, dw, kv, out_dtype=torch.float32)
