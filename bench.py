@@ -99,14 +99,19 @@ def main() -> int:
     L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
 
     kv = None
-    if args.paged:
+    f8 = None          # packed 8-bit cache
+    f8_paged = None    # (PagedSuffix of codes, k_scale, v_scale)
+    if args.paged and args.fp8_kv:
+        f8_paged = wl.make_paged_fp8(w, args.paged, reserve=args.append_steps)
+        pg8 = f8_paged[0]
+        kv = hb.PagedKV(K=torch.from_numpy(pg8.K).cuda(), V=torch.from_numpy(pg8.V).cuda(),
+                        page_table=torch.from_numpy(pg8.table).cuda(), page_size=pg8.page_size, kv_format=hb.HG_KV_E4M3,
+                        k_scale=f8_paged[1], v_scale=f8_paged[2])
+        torch.cuda.synchronize()
+    elif args.paged:
         kv = dev.paged_to_device(wl.make_paged(w, args.paged, reserve=args.append_steps))
         torch.cuda.synchronize()
-
-    f8 = None
-    if args.fp8_kv:
-        if args.paged:
-            raise SystemExit("--fp8-kv needs packed rows (no --paged)")
+    elif args.fp8_kv:
         f8 = wl.make_fp8(w, reserve=args.append_steps, junk_code=None)
         dK8, dV8 = torch.from_numpy(f8.Ks8).cuda(), torch.from_numpy(f8.Vs8).cuda()
         doff8 = torch.from_numpy(f8.offsets).cuda()
@@ -184,7 +189,7 @@ def main() -> int:
     B, Hq, Hkv, D, G = w.B, w.Hq, w.Hkv, w.D, w.G
     rows = B * Hq
     T = int(np.minimum(w.lengths, w.max_len).sum())
-    kv_elem = 1 if f8 is not None else 2
+    kv_elem = 1 if args.fp8_kv else 2
     suffix_bytes = 2 * kv_elem * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
     level_flops, level_bytes = [], []
     for lv in w.levels:
@@ -275,13 +280,17 @@ def main() -> int:
         c0 = time.perf_counter()
         Oref, Lref = oracle.attention(w, seqs=seqs)
         c1 = time.perf_counter()
-        if f8 is not None:
+        if args.fp8_kv:
             # the timed call read the 8-bit cache: its reference is the merge of the exact attention over the shared
             # levels and the exact attention over the decoded codes (the bf16 run above only times the oracle)
             from oracle import fp8 as ofp8
             Op, Lp = oracle.attention(w, suffix=False, seqs=seqs)
-            Os, Ls = ofp8.suffix_attention_fp8(w.Q[seqs], Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets[seqs],
-                                               w.lengths[seqs], w.scale)
+            if f8 is not None:
+                K8, V8, off8, ks8, vs8 = f8.Ks8, f8.Vs8, f8.offsets[seqs], f8.k_scale, f8.v_scale
+            else:
+                pg8, ks8, vs8 = f8_paged
+                K8, V8, off8 = oracle.paged_to_packed(pg8.K, pg8.V, pg8.table[seqs], pg8.page_size, w.lengths[seqs])
+            Os, Ls = ofp8.suffix_attention_fp8(w.Q[seqs], Hkv, K8, V8, ks8, vs8, off8, w.lengths[seqs], w.scale)
             Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
         cpu = {"value": len(seqs) / (c1 - c0), "unit": "queries/s per layer", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{len(seqs)} of {B} sequences (evenly spaced + shortest and longest suffix), all {Hq} heads, full key lists; "
@@ -293,7 +302,7 @@ def main() -> int:
         dL = float((np.abs(Lg - Lref) / np.abs(Lref)).max())
         rel = float(np.linalg.norm(Og - Oref) / np.linalg.norm(Oref))
         parity = {"max_abs_dO": dO, "max_rel_dLSE": dL, "rel_l2_O": rel, "max_abs_O": float(np.abs(Oref).max()), "sequences": len(seqs)}
-        if naive_ms is not None and f8 is None:    # the comparison call read the bf16 cache
+        if naive_ms is not None and not args.fp8_kv:    # the comparison call read the bf16 cache
             Ogn = On[idx].float().cpu().numpy().astype(np.float64)
             parity["naive_max_abs_dO"] = float(np.abs(Ogn - Oref).max())
         ok = dO <= 1e-2 and dL <= 1e-3 and rel <= 1e-2
@@ -308,7 +317,7 @@ def main() -> int:
         "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
                    "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
                    "suffix_len": [int(w.lengths.min()), int(w.lengths.max())], "suffix_tokens": int(w.T), "seed": w.seed,
-                   "overlap_streams": args.overlap, "suffix_cache": "packed rows, 8-bit E4M3 codes" if args.fp8_kv else f"paged, {args.paged} rows per page" if args.paged else "packed rows"},
+                   "overlap_streams": args.overlap, "suffix_cache": (f"paged, {args.paged} rows per page" if args.paged else "packed rows") + (", 8-bit E4M3 codes" if args.fp8_kv else "")},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -228,10 +228,7 @@ int hg_kv_append_paged(hg_ctx* ctx, const void* Knew, const void* Vnew, const hg
  * in hg_suffix_attn (offsets / lengths: DEVICE int32[B]).  Shared levels, Q and the results keep their formats.
  *   hg_suffix_attn_fp8 / hg_hydragen_attn_fp8: hg_suffix_attn / hg_hydragen_attn over such a cache: the attention
  *     of the decoded values (the codes are expanded exactly; all arithmetic is fp32).  Rows that no sequence owns
- *     may hold any code.  The vector-ALU suffix kernel runs whatever HG_OPT_SUFFIX_KERNEL says: with one query row per
- *     KV head (multi-head attention, one query per sequence) the call is bound by the bytes and gains from the
- *     smaller cache; with four or more rows per KV head (grouped heads, several queries) that kernel is bound by
- *     its arithmetic and the bf16 cache on the matrix-core kernel is faster (the 8-bit cache then saves memory only).
+ *     may hold any code.  The suffix kernel is chosen as for a bf16 cache (HG_OPT_SUFFIX_KERNEL).
  *   hg_kv_append_fp8: hg_kv_append with the new bf16 rows quantised on the way in:
  *     code = nearest E4M3 value to (x / scale) (fp32 quotient), ties to the even code, magnitudes above 448 -> 448.
  * Invalid scales (zero, negative, infinite, NaN) give HG_ERR_INVALID_ARG.
