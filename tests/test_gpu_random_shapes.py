@@ -1,5 +1,5 @@
-"""Seeded random shapes and option settings through the fused call, the comparison kernel and the paged variant,
-each against the fp64 oracle: tree depth 0..3 with unequal blocks and uncovered sequences, MHA and grouped heads,
+"""Seeded random shapes and option settings through the fused call, the comparison kernel, the paged variant and the
+8-bit suffix cache (packed and paged), each against the fp64 oracle: tree depth 0..3 with unequal blocks and uncovered sequences, MHA and grouped heads,
 1..6 queries per sequence, D in {64, 128}, ragged suffixes with empty ones, every kernel choice and split setting."""
 import sys
 
@@ -71,4 +71,26 @@ def test_random_shape(seed):
         O, L = dev.hydragen_paged(ctx, dw, kv, out_dtype=torch.float32)
         torch.cuda.synchronize()
         check(to_np(O), to_np(L), Oref, Lref, f"paged seed={seed}")
+        # the same suffix as an 8-bit cache, packed and through pages: reference = merge of the exact attention over
+        # the levels and over the decoded codes
+        from oracle import fp8
+        f8 = wl.make_fp8(w, reserve=int(rng.integers(0, 4)))
+        Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
+        if w.levels:
+            Op, Lp = oracle.attention(w, suffix=False)
+            O8ref, L8ref = oracle.merge([Op, Os], [Lp, Ls])
+        else:
+            O8ref, L8ref = Os, Ls
+        O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
+        L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+        hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, torch.from_numpy(f8.Ks8).cuda(), torch.from_numpy(f8.Vs8).cuda(), f8.k_scale,
+                                f8.v_scale, torch.from_numpy(f8.offsets).cuda(), dw.lengths, dw.max_len, O, L, dw.scale)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), O8ref, L8ref, f"fp8 seed={seed}")
+        pg8, ks8, vs8 = wl.make_paged_fp8(w, int(rng.choice([16, 64])))
+        kv8 = hb.PagedKV(K=torch.from_numpy(pg8.K).cuda(), V=torch.from_numpy(pg8.V).cuda(), page_table=torch.from_numpy(pg8.table).cuda(),
+                         page_size=pg8.page_size, kv_format=hb.HG_KV_E4M3, k_scale=ks8, v_scale=vs8)
+        O, L = dev.hydragen_paged(ctx, dw, kv8, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(O), to_np(L), O8ref, L8ref, f"paged fp8 seed={seed}")
     ctx.close()
