@@ -399,3 +399,58 @@ def test_paged_fp8_error_paths():
                                        dw.Hkv, dw.D, dw.scale, O.data_ptr(), hb.HG_F32, L.data_ptr())
     assert rc == hb.HG_ERR_INVALID_ARG
     ctx.close()
+
+
+@pytest.mark.parametrize("idx", [5, 4], ids=["tree_mha", "gqa"])
+def test_fp8_decode_steps_in_a_graph(idx):
+    """Quantising cache update + fused attention over the 8-bit cache, captured once and replayed: every step matches the
+    oracle's codes bit for bit and the oracle's attention over them."""
+    say(f"fp8 decode steps in a graph idx={idx}")
+    steps = 4
+    w = wl.scaled_down(idx)
+    dw = dev.to_device(w)
+    s = torch.cuda.Stream()
+    ctx = hb.Context(0, hb.hg_workspace_bytes(dw.B, dw.Hq, dw.D, 24), stream=s)
+    f8 = wl.make_fp8(w, reserve=steps, junk_code=None)
+    cap = f8.capacity
+    Kd, Vd, offs = u8(f8.Ks8), u8(f8.Vs8), i32(f8.offsets)
+    Kh, Vh, Lh = f8.Ks8, f8.Vs8, w.lengths.copy()
+    dlen = i32(w.lengths)
+    dKn = torch.zeros((w.B, w.Hkv, w.D), dtype=torch.bfloat16, device="cuda:0")
+    dVn = torch.zeros_like(dKn)
+    O = torch.zeros((dw.B, dw.Hq, dw.D), dtype=torch.float32, device="cuda:0")
+    L = torch.zeros((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        hb.hg_kv_append_fp8(ctx, dKn, dVn, Kd, Vd, f8.k_scale, f8.v_scale, offs, dlen, cap)
+        hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, Kd, Vd, f8.k_scale, f8.v_scale, offs, dlen, cap, O, L, dw.scale)
+
+    Op, Lp = oracle.attention(w, suffix=False)
+    g = None
+    for k in range(steps):
+        Kn, Vn = wl.new_rows(w, step=k)
+        dKn.copy_(dev.bf16_tensor(Kn, "cuda:0"))
+        dVn.copy_(dev.bf16_tensor(Vn, "cuda:0"))
+        torch.cuda.synchronize()
+        if k == 0:
+            with torch.cuda.stream(s):   # first step eagerly (one-time kernel attribute set-up happens outside capture)
+                step()
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+        elif k == 1:
+            with torch.cuda.graph(g, stream=s):
+                step()
+            torch.cuda.synchronize()
+            g.replay()                   # capture does not execute: this replay is step 1
+        else:
+            g.replay()
+        torch.cuda.synchronize()
+        Kh, Vh, Lh = fp8.kv_append_fp8(Kh, Vh, f8.offsets, Lh, cap, wl.bf16_bits_to_f32(Kn), wl.bf16_bits_to_f32(Vn),
+                                       f8.k_scale, f8.v_scale)
+        assert np.array_equal(dlen.cpu().numpy(), Lh), f"lengths after step {k}"
+        assert np.array_equal(Kd.cpu().numpy(), Kh) and np.array_equal(Vd.cpu().numpy(), Vh), f"codes after step {k}"
+        Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, Kh, Vh, f8.k_scale, f8.v_scale, f8.offsets, Lh, w.scale)
+        Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
+        check(to_np(O), to_np(L), Oref, Lref, f"fp8 graph decode step {k}")
+    assert np.array_equal(Lh, w.lengths + steps)
+    ctx.close()
