@@ -19,10 +19,11 @@
 // suffix rows [0, length - (nq-1-t)), applied as a per-lane bound on the key index in the stages that reach it.
 //
 // FP8: the suffix rows are 8-bit E4M3 codes (one fp32 scale per tensor; not in the paper).  A K/V ring element is then
-// 4 KiB + 4 KiB of codes (half the copy instructions); before a stage is multiplied the wavefront expands it into one
-// bf16 work stage in LDS with the layout the bf16 path reads (v_cvt_scalef32_pk_bf16_fp8, exact: every E4M3 value
-// is a bf16 value), so the products and the softmax are the same code.  The K scale multiplies the softmax scale,
-// the V scale the final normalisation.
+// 4 KiB + 4 KiB of codes (half the copy instructions).  K fragments are read as 8 bytes of codes and expanded in
+// registers (v_cvt_scalef32_pk_bf16_fp8, exact: every E4M3 value is a bf16 value); the V codes of a stage are
+// expanded into one bf16 work stage in LDS with the layout the transposing reads expect.  Products, masks and
+// softmax are the same code.  The K scale multiplies the softmax scale, the V scale the final normalisation.
+// 24 KiB of LDS per wavefront (2 x 8 KiB ring + 8 KiB work stage).
 #include "hg_internal.h"
 #include "prefix_common.h"
 
@@ -71,10 +72,9 @@ template <int NS, bool PAGED, bool SEG, bool FP8 = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
     static_assert(!(FP8 && SEG), "shared levels are bf16");
-    // bf16: ring slot n holds K (or Q) at n * STB and V at VRING + n * STB.  FP8: ring slot n holds the K codes at
-    // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot); the bf16 work stage that the products
-    // read is K at NS * STB and V at (NS + 1) * STB.  Either way 2 * NS * STB bytes when NS = 2.
-    constexpr int VRING = FP8 ? STB : NS * STB;    // from the K stage the products read to its V stage
+    // bf16: ring slot n holds K (or Q) at n * STB and V at (NS + n) * STB.  FP8: ring slot n holds the K codes at
+    // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot); the bf16 V stage that the second
+    // product reads is the work stage at NS * STB.
     constexpr int ES = FP8 ? 1 : 2;                // bytes per cache element
     constexpr int CPRG = D * ES / 16;              // 16-byte chunks per cache row
     constexpr int RPIG = 64 / CPRG;                // cache rows one copy instruction covers
@@ -188,9 +188,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     };
 
     // ---- LDS fragment addresses (relative to the slot), as in prefix_wide.hip ------------------------------------------
-    unsigned kaddr[KS];
+    unsigned kaddr[KS], qaddr[KS];     // K fragments of a stage, Q fragments of a tile (bf16: the same addresses)
 #pragma unroll
-    for (int s = 0; s < KS; ++s) kaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    for (int s = 0; s < KS; ++s) kaddr[s] = qaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    // FP8: the 8 codes of K row lq, columns 16 s + 8 hl .. +7: rows lie in copy order (row r at (r/8) KiB + (r%8) 128 B),
+    // their 16-byte chunks XOR-swizzled by (r/2) % 8 on the global side so that 16 consecutive lanes hit 32 different banks
+    if (FP8) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            kaddr[s] = (unsigned)((lq >> 3) * 1024 + (lq & 7) * 128 + ((s ^ ((lq >> 1) & 7)) * 16) + 8 * hl);
+    }
     unsigned vaddr[DB];
     {
         const int i16 = l & 15, g1 = (l >> 4) & 1;
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);
-            vaddr[db] = (unsigned)(VRING + keyq * ROWB + ((chunk ^ fv) * 16) + (i16 & 1) * 8);
+            vaddr[db] = (unsigned)(keyq * ROWB + ((chunk ^ fv) * 16) + (i16 & 1) * 8);   // relative to the V stage
         }
     }
 
@@ -229,9 +236,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 const int srow = i * RPIG + lrowg;
                 const unsigned ro = (unsigned)min(srow, rowclamp) * rstride_b;
                 if (FP8) {
-                    // codes land in copy order (lane l of copy i holds row 8i + l/8, bytes 16 (l%8) ..): the expansion
-                    // reads them back the same way and applies the swizzles when it writes the bf16 stage
-                    voffK[i] = voffV[i] = ro + (unsigned)(schg * 16);
+                    // codes land in copy order (lane l of copy i holds row 8i + l/8): K chunks swizzled for the fragment
+                    // reads; V chunks as they are, the expansion reads them back lane by lane and applies the V
+                    // swizzle when it writes the bf16 work stage
+                    voffK[i] = ro + (unsigned)((schg ^ ((srow >> 1) & 7)) * 16);
+                    voffV[i] = ro + (unsigned)(schg * 16);
                 } else {
                     voffK[i] = ro + (unsigned)((sch ^ (srow % CPR)) * 16);
                     voffV[i] = ro + (unsigned)((sch ^ (4 * (srow % 4))) * 16);
@@ -393,7 +402,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             wait_for(pending);
             lane_of(cit);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + kaddr[s]));
+            for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + qaddr[s]));
 #pragma unroll
             for (int i = 0; i < DB; ++i)
 #pragma unroll
@@ -408,37 +417,43 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         } else {
             pending -= KVOPS;
             wait_for(pending);
+            unsigned char* const vstage = smem + (FP8 ? NS * STB : (sb - smem) + NS * STB);   // the bf16 V stage of this element
             if constexpr (FP8) {
-                // expand the codes of this element into the bf16 work stage: lane l of copy i holds row 8i + l/8,
+                // expand the V codes of this element into the bf16 work stage: lane l of copy i holds row 8i + l/8,
                 // columns 16 (l%8) .. +15, i.e. the two 16-byte chunks 2 (l%8) and 2 (l%8) + 1 of the bf16 row
-                unsigned char* const wk = smem + NS * STB;
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
+                for (int i = 0; i < CPSG; ++i) {
+                    const uintx4 raw = *reinterpret_cast<const uintx4*>(sb + VSLOT + i * 1024 + l * 16);
+                    unsigned w[8];
 #pragma unroll
-                    for (int i = 0; i < CPSG; ++i) {
-                        const uintx4 raw = *reinterpret_cast<const uintx4*>(sb + t * VSLOT + i * 1024 + l * 16);
-                        unsigned w[8];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            w[2 * j] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, false));
-                            w[2 * j + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
-                        }
-                        const int row = i * RPIG + lrowg;
-                        const int swz = t == 0 ? row % CPR : 4 * (row % 4);
-                        unsigned char* const rowp = wk + t * VRING + row * ROWB;
-                        *reinterpret_cast<uintx4*>(rowp + (((2 * schg) ^ swz) * 16)) = uintx4{w[0], w[1], w[2], w[3]};
-                        *reinterpret_cast<uintx4*>(rowp + (((2 * schg + 1) ^ swz) * 16)) = uintx4{w[4], w[5], w[6], w[7]};
+                    for (int j = 0; j < 4; ++j) {
+                        w[2 * j] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, false));
+                        w[2 * j + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
                     }
+                    const int row = i * RPIG + lrowg;
+                    const int swz = 4 * (row % 4);
+                    unsigned char* const rowp = vstage + row * ROWB;
+                    *reinterpret_cast<uintx4*>(rowp + (((2 * schg) ^ swz) * 16)) = uintx4{w[0], w[1], w[2], w[3]};
+                    *reinterpret_cast<uintx4*>(rowp + (((2 * schg + 1) ^ swz) * 16)) = uintx4{w[4], w[5], w[6], w[7]};
                 }
             }
-            const unsigned char* const fb = FP8 ? smem + NS * STB : sb;    // the bf16 stage the products read
             // S^T = K Q^T
             floatx16 S;
 #pragma unroll
             for (int i = 0; i < 16; ++i) S[i] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const uintx4 kv = *reinterpret_cast<const uintx4*>(fb + kaddr[s]);
+                uintx4 kv;
+                if constexpr (FP8) {
+                    const unsigned __attribute__((ext_vector_type(2))) kc =
+                        *reinterpret_cast<const unsigned __attribute__((ext_vector_type(2)))*>(sb + kaddr[s]);
+                    kv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, false));
+                    kv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, true));
+                    kv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, false));
+                    kv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, true));
+                } else {
+                    kv = *reinterpret_cast<const uintx4*>(sb + kaddr[s]);
+                }
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S, 0, 0, 0);
             }
             // keys outside [key0, min(ke, vis_end)): stage rows before the stage's first key (window clamp), rows past
@@ -457,7 +472,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // the rows past the range are a page's unwritten tail (or another page altogether): clear their V rows
                 // in LDS, since their zero probabilities would still turn a NaN into a NaN in the second product
                 const int nhi = cit.ke - key0;
-                unsigned char* const vs = smem + (fb - smem) + VRING;
+                unsigned char* const vs = vstage;
 #pragma unroll
                 for (int i = 0; i < CPS; ++i) {
                     const int row = i * RPI + lrow;
@@ -469,7 +484,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // sequence's slot of the cache, possibly padding that was never written.  Their probabilities are
                 // zero, but 0 * NaN is NaN in the second product: clear those V rows in LDS.
                 const int nlo = key0 - k0c;
-                unsigned char* const vs = smem + (fb - smem) + VRING;
+                unsigned char* const vs = vstage;
 #pragma unroll
                 for (int i = 0; i < CPS; ++i) {
                     const int row = i * RPI + lrow;
@@ -509,7 +524,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const unsigned char* vp = fb + vaddr[db] + tt * 16 * ROWB;
+                    const unsigned char* vp = vstage + vaddr[db] + tt * 16 * ROWB;
                     const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
                     const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
                     const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -559,8 +574,8 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
     if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
     if (a.fp8) {
         if (a.seg) return hipErrorInvalidValue;
-        if (a.pg.table) decode_mfma_kernel<NS, true, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
-        else decode_mfma_kernel<NS, false, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        if (a.pg.table) decode_mfma_kernel<NS, true, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
+        else decode_mfma_kernel<NS, false, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
     } else if (a.pg.table) {
         decode_mfma_kernel<NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else if (a.seg) {
