@@ -45,7 +45,39 @@ def test_constants_match_header():
     text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
     for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_F32", "HG_BF16",
                  "HG_MAX_LEVELS", "HG_MAX_PARTS", "HG_OPT_PREFIX_SPLITS", "HG_OPT_SUFFIX_CHUNK", "HG_OPT_OVERLAP",
-                 "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_OPT_PREFIX_KERNEL", "HG_TIMING_RING"):
+                 "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_OPT_PREFIX_KERNEL", "HG_TIMING_RING", "HG_OPT_WIDE_SLOTS",
+                 "HG_OPT_NUM_QUERIES", "HG_OPT_SUFFIX_KERNEL", "HG_OPT_SUFFIX_ITEMS_PER_WAVE", "HG_KV_BF16", "HG_KV_E4M3"):
         m = re.search(rf"\b{name}\s*=\s*(\d+)", text)
         assert m, name
         assert int(m.group(1)) == getattr(hb, name), name
+
+
+def test_paged_struct_layout_matches_header():
+    """hg_paged_kv is passed by pointer: the ctypes mirror must have the header's fields in the header's order."""
+    text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} hg_paged_kv;", text).group(1)
+    names = re.findall(r"(\w+);", body)
+    assert names == [f[0] for f in hb.hg_paged_kv._fields_]
+    body = re.search(r"typedef struct \{([^}]*)\} hg_level;", text).group(1)
+    assert re.findall(r"(\w+);", body) == [f[0] for f in hb.hg_level._fields_]
+
+
+def test_calls_without_a_context_are_rejected_before_any_device_work(lib):
+    """Every compute entry point checks its context first: a null context is an argument error, with no GPU present."""
+    import ctypes
+    z = ctypes.c_void_p(0)
+    kv = hb.hg_paged_kv(0, 0, 0, 16, 1, 1, 0, 1.0, 1.0)
+    lv = hb.hg_level()
+    bad = hb.HG_ERR_INVALID_ARG
+    assert lib.hg_prefix_attn(z, z, z, z, 1, 1, 1, 128, 1, 0.0, z, 0, z) == bad
+    assert lib.hg_suffix_attn(z, z, z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_suffix_attn_fp8(z, z, z, z, 1.0, 1.0, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_hydragen_attn(z, z, 0, ctypes.byref(lv), z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_hydragen_attn_fp8(z, z, 0, ctypes.byref(lv), z, z, 1.0, 1.0, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_naive_attn(z, z, 0, ctypes.byref(lv), z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_suffix_attn_paged(z, z, ctypes.byref(kv), z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_kv_append(z, z, z, z, z, z, z, 1, 1, 1, 128) == bad
+    assert lib.hg_kv_append_fp8(z, z, z, z, z, 1.0, 1.0, z, z, 1, 1, 1, 128) == bad
+    # scales are checked even before the context
+    assert lib.hg_suffix_attn_fp8(z, z, z, z, 0.0, 1.0, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_kv_append_fp8(z, z, z, z, z, 1.0, float("nan"), z, z, 1, 1, 1, 128) == bad
