@@ -168,11 +168,16 @@ struct SuffixPlan { int chunk, nchunks, gt; bool mfma; int ipw; };
 // Storage format of the suffix cache: bf16 rows, or E4M3 codes with one scale per tensor (value = code * scale).
 struct KvFmt { int fp8 = 0; float k_scale = 1.f, v_scale = 1.f; };
 
+// Automatic choice between the two per-sequence kernels for D = 128.  The matrix-core kernel reads every K/V row
+// once for all nq * G query rows that a KV head serves; the vector-ALU kernel pays one dot product per row and key
+// and, across queries, re-reads the suffix.  Measured (B = 512, lengths up to 512, matrix-core against vector-ALU):
+// nq = 2: 184 against 368 us; G = 3: 96 against 211 us; G = 2: 94 against 114 us, but 178 against 153 us when no
+// sequence has more than 128 rows (the per-item cost of the matrix-core kernel); one row: the vector-ALU kernel.
+bool auto_mfma(int nq, int G, int max_len) { return nq >= 2 || G >= 3 || (G == 2 && max_len >= 256); }
+
 // Work items of the suffix kernel are (sequence, query, KV head, group of query heads, key chunk), one wavefront
 // each, in the vector-ALU kernel, and (sequence, KV head, 32-row tile of the nq * G rows, key chunk) in the
-// matrix-core kernel.  The matrix-core kernel (D = 128, packed rows) takes over when a KV head serves four or more
-// query rows of a sequence (grouped-query attention, several queries per sequence): the vector-ALU kernel is then
-// bound by its dot products, not by HBM, and re-reads the suffix once per query.  HG_OPT_SUFFIX_KERNEL forces either.
+// matrix-core kernel (D = 128; chosen by auto_mfma, HG_OPT_SUFFIX_KERNEL forces either).
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
 // max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
@@ -184,7 +189,7 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
     (void)fp8;   // both kernels read either cache format
-    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || R >= 4);
+    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len));
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
@@ -848,7 +853,7 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (parts.cap < 1) return HG_ERR_WORKSPACE;
     if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
     if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
-    if (D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || nq * G >= 4)) {
+    if (D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, (int)nmax))) {
         // Several query rows per KV head: the per-sequence kernel on the matrix cores, once per level (every sequence
         // walks the block that covers it by itself) and once for the suffix, each writing its own partial results.
         int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 1024;
