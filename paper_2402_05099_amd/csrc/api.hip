@@ -623,8 +623,11 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
             const long long tiles = (seqs * nq * G + kPrefixRowsWide - 1) / kPrefixRowsWide;
             if (seqs * nq * G > kPrefixRowsNarrow && tiles <= 32 && tiles > T) T = (int)tiles;
         }
-        // K and V, bf16 (or 8-bit codes); mean length taken as 0.75 max_len
-        const double bytes = (fmt.fp8 ? 2.0 : 4.0) * B * nq * (0.75 * max_len) * Hkv * D;
+        // K and V, bf16 (or 8-bit codes; on the matrix cores their expansion costs about a third of the saving); the
+        // vector-ALU kernel reads them once per query; mean length taken as 0.75 max_len
+        const bool sfx_mfma = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, 1 << 30, fmt.fp8 != 0).mfma;
+        const double per_elem = fmt.fp8 ? (sfx_mfma ? 2.6 : 2.0) : 4.0;
+        const double bytes = per_elem * B * (sfx_mfma ? 1 : nq) * (0.75 * max_len) * Hkv * D;
         wide_slots = pick_wide_slots(flops, bytes, T);
         tiny = c->opt_overlap == 0 && flops / 1.14e15 + bytes / 6.0e12 < 60e-6;
         if (tiny) wide_slots = 32;
