@@ -36,18 +36,24 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char*
     return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
 }
 
-template <int D, int GT>
+// Columns of a row that one lane owns: 8 (one 16-byte load of bf16, one 8-byte load of codes), or 16 codes (one
+// 16-byte load) where registers allow: an 8-bit row of D = 128 is then covered by 8 lanes, a wave-wide load brings 8
+// keys instead of 4, and the per-key overhead (cross-lane sum, exponential, masks) halves per byte.
+template <int D, int GT, bool FP8>
+constexpr int epl_of() { return (FP8 && D == 128 && GT <= 2) ? 16 : 8; }
+
+template <int D, int GT, int EPL = 8>
 struct DecodeState {
-    float q[GT][8];    // query elements of this lane's 8-wide column slice, pre-multiplied by scale*log2(e)
-    float m[GT];       // running max (log2 domain)
-    float l[GT];       // running sum of 2^(s-m)
-    float acc[GT][8];  // running sum of 2^(s-m) * v
+    float q[GT][EPL];    // query elements of this lane's column slice, pre-multiplied by scale*log2(e)
+    float m[GT];         // running max (log2 domain)
+    float l[GT];         // running sum of 2^(s-m)
+    float acc[GT][EPL];  // running sum of 2^(s-m) * v
 };
 
 // One batch of U wave-wide loads: KPW keys each, K and V rows of this lane's 8-column slice.
-template <int D, int U, bool FP8>
+template <int D, int U, bool FP8, int EPL = 8>
 struct KVBatch {
-    using Row = std::conditional_t<FP8, uint2, uint4>;   // this lane's 8 elements of a row
+    using Row = std::conditional_t<FP8 && EPL == 8, uint2, uint4>;   // this lane's EPL elements of a row
     Row k[U], v[U];
 };
 
@@ -70,9 +76,9 @@ __device__ __forceinline__ uint2 ldg64(const unsigned char* base, unsigned off) 
     const u32x2 v = STREAM ? __builtin_nontemporal_load(p) : *p;
     return make_uint2(v.x, v.y);
 }
-template <bool STREAM, bool FP8>
+template <bool STREAM, bool HALF>
 __device__ __forceinline__ auto ldg_row(const unsigned char* base, unsigned off) {
-    if constexpr (FP8) return ldg64<STREAM>(base, off);
+    if constexpr (HALF) return ldg64<STREAM>(base, off);
     else return ldg128<STREAM>(base, off);
 }
 
@@ -81,6 +87,15 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8]) {
     f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
     f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+}
+// 16 codes
+__device__ __forceinline__ void unpack8(const uint4& r, float (&f)[16]) {
+    const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[j], false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[j], true);
+        f[4 * j] = a.x; f[4 * j + 1] = a.y; f[4 * j + 2] = b.x; f[4 * j + 3] = b.y;
+    }
 }
 __device__ __forceinline__ void unpack8(const uint2& r, float (&f)[8]) {
     const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
@@ -92,36 +107,36 @@ __device__ __forceinline__ void unpack8(const uint2& r, float (&f)[8]) {
 // of its key in load 0 of the batch (sub-row, column slice and batch start); colb: the column part alone.  Lanes
 // whose key lies past the span read the span's first row instead (always valid; their score is masked), so no
 // load is predicated and a batch may be requested past the end of the span.
-template <int D, int U, bool STREAM, bool FP8>
-__device__ __forceinline__ void load_batch(KVBatch<D, U, FP8>& bt, const unsigned char* __restrict__ kb,
+template <int D, int U, bool STREAM, bool FP8, int EPL>
+__device__ __forceinline__ void load_batch(KVBatch<D, U, FP8, EPL>& bt, const unsigned char* __restrict__ kb,
                                            const unsigned char* __restrict__ vb, unsigned rstride_b, unsigned rowoff,
                                            unsigned colb, int first, int n) {
-    constexpr int KPW = 64 / (D / 8);
+    constexpr int KPW = 64 / (D / EPL);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int i = first + u * KPW;   // `first` already includes this lane's sub-row
         const unsigned off = i < n ? (unsigned)(u * KPW) * rstride_b + rowoff : colb;
-        bt.k[u] = ldg_row<STREAM, FP8>(kb, off);
-        bt.v[u] = ldg_row<STREAM, FP8>(vb, off);
+        bt.k[u] = ldg_row<STREAM, FP8 && EPL == 8>(kb, off);
+        bt.v[u] = ldg_row<STREAM, FP8 && EPL == 8>(vb, off);
     }
 }
 
 // online-softmax update of the state with one batch (keys first + u*KPW, masked beyond n)
-template <int D, int GT, int U, bool FP8>
-__device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBatch<D, U, FP8>& bt, int first, int n) {
-    constexpr int LPR = D / 8;
+template <int D, int GT, int U, bool FP8, int EPL>
+__device__ __forceinline__ void consume_batch(DecodeState<D, GT, EPL>& st, const KVBatch<D, U, FP8, EPL>& bt, int first, int n) {
+    constexpr int LPR = D / EPL;
     constexpr int KPW = 64 / LPR;
     float s[U][GT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const bool ok = first + u * KPW < n;
-        float k[8];
+        float k[EPL];
         unpack8(bt.k[u], k);
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             float d = st.q[g][0] * k[0];
 #pragma unroll
-            for (int j = 1; j < 8; ++j) d = fmaf(st.q[g][j], k[j], d);
+            for (int j = 1; j < EPL; ++j) d = fmaf(st.q[g][j], k[j], d);
             d = row_allreduce_sum<LPR>(d);
             s[u][g] = ok ? d : -INFINITY;
         }
@@ -143,13 +158,13 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBa
         }
         st.l[g] = fmaf(st.l[g], alpha, ps);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) st.acc[g][j] *= alpha;
+        for (int j = 0; j < EPL; ++j) st.acc[g][j] *= alpha;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float v[8];
+            float v[EPL];
             unpack8(bt.v[u], v);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) st.acc[g][j] = fmaf(p[u], v[j], st.acc[g][j]);
+            for (int j = 0; j < EPL; ++j) st.acc[g][j] = fmaf(p[u], v[j], st.acc[g][j]);
         }
     }
 }
@@ -157,18 +172,18 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT>& st, const KVBa
 // Online-softmax pass over `n` consecutive KV rows starting at row0, KV head kvh.  Software pipelined: the
 // loads of the next batch are issued before the current batch is consumed, so a wavefront always has a
 // batch in flight while it computes.
-template <int D, int GT, bool STREAM, bool FP8 = false>
-__device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
+template <int D, int GT, bool STREAM, bool FP8 = false, int EPL = 8>
+__device__ __forceinline__ void decode_span(DecodeState<D, GT, EPL>& st, const uint16_t* __restrict__ K,
                                             const uint16_t* __restrict__ V, int64_t row0, int n, int Hkv, int kvh,
                                             int lane) {
-    constexpr int LPR = D / 8;
+    constexpr int LPR = D / EPL;
     constexpr int KPW = 64 / LPR;
-    constexpr int U = GT >= 8 ? 2 : 4;
+    constexpr int U = (GT >= 8 ? 2 : 4) / (EPL / 8);   // the same keys per batch whatever a lane owns of a row
     constexpr int STEP = KPW * U;
     constexpr unsigned ES = FP8 ? 1u : 2u;     // bytes per element
     const int sub = lane / LPR;
     const unsigned rstride_b = (unsigned)Hkv * D * ES;
-    const unsigned colb = (unsigned)(lane % LPR) * 8u * ES;
+    const unsigned colb = (unsigned)(lane % LPR) * EPL * ES;
     unsigned rowoff = (unsigned)sub * rstride_b + colb;
     const int64_t first_b = (row0 * Hkv + kvh) * (int64_t)D * ES;
     const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K) + first_b);
@@ -176,38 +191,38 @@ __device__ __forceinline__ void decode_span(DecodeState<D, GT>& st, const uint16
     const unsigned step_b = (unsigned)STEP * rstride_b;
 
     // every load is issued unconditionally (see load_batch), so the wait counts the compiler derives are exact
-    KVBatch<D, U, FP8> ba, bb;
-    load_batch<D, U, STREAM, FP8>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
+    KVBatch<D, U, FP8, EPL> ba, bb;
+    load_batch<D, U, STREAM, FP8, EPL>(ba, kb, vb, rstride_b, rowoff, colb, sub, n);
     for (int it = 0; it < n; it += 2 * STEP) {
         rowoff += step_b;
-        load_batch<D, U, STREAM, FP8>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
+        load_batch<D, U, STREAM, FP8, EPL>(bb, kb, vb, rstride_b, rowoff, colb, it + STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the arithmetic that hides their latency
-        consume_batch<D, GT, U, FP8>(st, ba, it + sub, n);
+        consume_batch<D, GT, U, FP8, EPL>(st, ba, it + sub, n);
         rowoff += step_b;
         __builtin_amdgcn_sched_barrier(0);
-        load_batch<D, U, STREAM, FP8>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
+        load_batch<D, U, STREAM, FP8, EPL>(ba, kb, vb, rstride_b, rowoff, colb, it + 2 * STEP + sub, n);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + STEP < n) consume_batch<D, GT, U, FP8>(st, bb, it + STEP + sub, n);
+        if (it + STEP < n) consume_batch<D, GT, U, FP8, EPL>(st, bb, it + STEP + sub, n);
     }
 }
 
 // The same pass over rows [start, start+n) of sequence b's suffix when the rows live in a paged pool (`start` is a
 // multiple of 32, the span touches at most 64 pages: the host bounds the chunk by 32 pages).  Lane i of the
-// wavefront holds the physical page of the span's i-th logical page; the 4 or 8 keys of one wave-wide load never
+// wavefront holds the physical page of the span's i-th logical page; the 4 or 8 keys of one wave-wide load (64 lanes / lanes per row) never
 // straddle a page (pages hold at least 16 rows), so the page of a load is wavefront-uniform: one v_readlane and
 // a few scalar instructions per load, the same unpredicated vector loads and the same pipeline as above.
-template <int D, int GT, bool FP8 = false>
-__device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const uint16_t* __restrict__ K,
+template <int D, int GT, bool FP8 = false, int EPL = 8>
+__device__ __forceinline__ void decode_span_paged(DecodeState<D, GT, EPL>& st, const uint16_t* __restrict__ K,
                                                   const uint16_t* __restrict__ V, const PagedDev& pg, int b, int start,
                                                   int n, int Hkv, int kvh, int lane) {
-    constexpr int LPR = D / 8;
+    constexpr int LPR = D / EPL;
     constexpr int KPW = 64 / LPR;
-    constexpr int U = GT >= 8 ? 2 : 4;
+    constexpr int U = (GT >= 8 ? 2 : 4) / (EPL / 8);
     constexpr int STEP = KPW * U;
     constexpr unsigned ES = FP8 ? 1u : 2u;     // bytes per element
     const int sub = lane / LPR;
     const unsigned rstride_b = (unsigned)Hkv * D * ES;
-    const unsigned colb = (unsigned)(lane % LPR) * 8u * ES;
+    const unsigned colb = (unsigned)(lane % LPR) * EPL * ES;
     const unsigned subrow = (unsigned)sub * rstride_b + colb;
     const unsigned char* kb = uniform_ptr(reinterpret_cast<const unsigned char*>(K) + (int64_t)kvh * D * ES);
     const unsigned char* vb = uniform_ptr(reinterpret_cast<const unsigned char*>(V) + (int64_t)kvh * D * ES);
@@ -224,26 +239,26 @@ __device__ __forceinline__ void decode_span_paged(DecodeState<D, GT>& st, const 
         return ((unsigned)(page << shift) + (unsigned)(pos & ((1 << shift) - 1))) * rstride_b;
     };
     const unsigned safe = row_base(0) + colb;   // lanes past the span read its first row (their scores are masked)
-    auto load = [&](KVBatch<D, U, FP8>& bt, int i0) {
+    auto load = [&](KVBatch<D, U, FP8, EPL>& bt, int i0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int iu = i0 + u * KPW;
             const unsigned off = iu + sub < n ? row_base(iu) + subrow : safe;
-            bt.k[u] = ldg_row<true, FP8>(kb, off);
-            bt.v[u] = ldg_row<true, FP8>(vb, off);
+            bt.k[u] = ldg_row<true, FP8 && EPL == 8>(kb, off);
+            bt.v[u] = ldg_row<true, FP8 && EPL == 8>(vb, off);
         }
     };
 
-    KVBatch<D, U, FP8> ba, bb;
+    KVBatch<D, U, FP8, EPL> ba, bb;
     load(ba, 0);
     for (int it = 0; it < n; it += 2 * STEP) {
         load(bb, it + STEP);
         __builtin_amdgcn_sched_barrier(0);
-        consume_batch<D, GT, U, FP8>(st, ba, it + sub, n);
+        consume_batch<D, GT, U, FP8, EPL>(st, ba, it + sub, n);
         __builtin_amdgcn_sched_barrier(0);
         load(ba, it + 2 * STEP);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + STEP < n) consume_batch<D, GT, U, FP8>(st, bb, it + STEP + sub, n);
+        if (it + STEP < n) consume_batch<D, GT, U, FP8, EPL>(st, bb, it + STEP + sub, n);
     }
 }
 
@@ -275,7 +290,8 @@ __device__ __forceinline__ void block_of(const LevelDev& lv, int b, int B, int& 
 // FP8 (only without SHARED): the suffix rows are E4M3 codes; a key is code * a.k_scale, a value code * a.v_scale.
 template <int D, int GT, bool SHARED, bool PAGED, bool FP8 = false>
 __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
-    constexpr int LPR = D / 8;
+    constexpr int EPL = epl_of<D, GT, FP8>();   // columns per lane
+    constexpr int LPR = D / EPL;                // lanes per row
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int64_t u = (int64_t)blockIdx.x * 4 + wave;
@@ -289,21 +305,25 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
     const int tq = bq % a.nq;
     const int h0 = kvh * a.G + gb * GT;  // first query head of this work item
 
-    DecodeState<D, GT> st;
+    DecodeState<D, GT, EPL> st;
     {
         const float qs = FP8 ? a.scale * kLog2e * a.k_scale : a.scale * kLog2e;
-        const int col = (lane % LPR) * 8;
+        const int col = (lane % LPR) * EPL;
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            const uint4 qv = *reinterpret_cast<const uint4*>(a.Q + ((int64_t)bq * a.Hq + h0 + g) * D + col);
-            st.q[g][0] = bf16_lo(qv.x) * qs; st.q[g][1] = bf16_hi(qv.x) * qs;
-            st.q[g][2] = bf16_lo(qv.y) * qs; st.q[g][3] = bf16_hi(qv.y) * qs;
-            st.q[g][4] = bf16_lo(qv.z) * qs; st.q[g][5] = bf16_hi(qv.z) * qs;
-            st.q[g][6] = bf16_lo(qv.w) * qs; st.q[g][7] = bf16_hi(qv.w) * qs;
+#pragma unroll
+            for (int h8 = 0; h8 < EPL / 8; ++h8) {
+                const uint4 qv = *reinterpret_cast<const uint4*>(a.Q + ((int64_t)bq * a.Hq + h0 + g) * D + col + 8 * h8);
+                float* const q = &st.q[g][8 * h8];
+                q[0] = bf16_lo(qv.x) * qs; q[1] = bf16_hi(qv.x) * qs;
+                q[2] = bf16_lo(qv.y) * qs; q[3] = bf16_hi(qv.y) * qs;
+                q[4] = bf16_lo(qv.z) * qs; q[5] = bf16_hi(qv.z) * qs;
+                q[6] = bf16_lo(qv.w) * qs; q[7] = bf16_hi(qv.w) * qs;
+            }
             st.m[g] = -INFINITY;
             st.l[g] = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) st.acc[g][j] = 0.f;
+            for (int j = 0; j < EPL; ++j) st.acc[g][j] = 0.f;
         }
     }
 
@@ -314,7 +334,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         int begin, count;
         block_of(a.lv[li], b, a.B, begin, count);
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
-        if (s0 < s1) decode_span<D, GT, false>(st, a.lv[li].K, a.lv[li].V, begin + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+        if (s0 < s1) decode_span<D, GT, false, false, EPL>(st, a.lv[li].K, a.lv[li].V, begin + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
         pos += count;
     }
     if (a.lengths) {
@@ -323,8 +343,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         if (count < 0) count = 0;
         const int64_t s0 = max(lo, pos), s1 = min(hi, pos + count);
         if (s0 < s1) {
-            if constexpr (PAGED) decode_span_paged<D, GT, FP8>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
-            else decode_span<D, GT, true, FP8>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
+            if constexpr (PAGED) decode_span_paged<D, GT, FP8, EPL>(st, a.Ks, a.Vs, a.pg, b, (int)s0, (int)(s1 - s0), a.Hkv, kvh, lane);
+            else decode_span<D, GT, true, FP8, EPL>(st, a.Ks, a.Vs, a.offsets[b] + (s0 - pos), (int)(s1 - s0), a.Hkv, kvh, lane);
         }
     }
 
@@ -339,9 +359,9 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         float l = st.l[g] * f;
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1) l += __shfl_xor(l, off);
-        float o[8];
+        float o[EPL];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < EPL; ++j) {
             o[j] = st.acc[g][j] * f;
 #pragma unroll
             for (int off = LPR; off < 64; off <<= 1) o[j] += __shfl_xor(o[j], off);
@@ -349,16 +369,20 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
         if (lane < LPR) {
             const float inv = l > 0.f ? (FP8 ? a.v_scale / l : 1.0f / l) : 0.f;
             const int64_t idx = (int64_t)bq * a.Hq + h0 + g;
-            const int64_t e = (int64_t)c * a.out.part_stride_O + idx * D + lane * 8;
-            if (a.out.bf16) {
-                uint4 v;
-                v.x = pack_bf16(o[0] * inv, o[1] * inv); v.y = pack_bf16(o[2] * inv, o[3] * inv);
-                v.z = pack_bf16(o[4] * inv, o[5] * inv); v.w = pack_bf16(o[6] * inv, o[7] * inv);
-                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(a.out.O) + e) = v;
-            } else {
-                float* op = static_cast<float*>(a.out.O) + e;
-                *reinterpret_cast<float4*>(op) = make_float4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
-                *reinterpret_cast<float4*>(op + 4) = make_float4(o[4] * inv, o[5] * inv, o[6] * inv, o[7] * inv);
+#pragma unroll
+            for (int h8 = 0; h8 < EPL / 8; ++h8) {
+                const int64_t e = (int64_t)c * a.out.part_stride_O + idx * D + lane * EPL + 8 * h8;
+                const float* const oh = &o[8 * h8];
+                if (a.out.bf16) {
+                    uint4 v;
+                    v.x = pack_bf16(oh[0] * inv, oh[1] * inv); v.y = pack_bf16(oh[2] * inv, oh[3] * inv);
+                    v.z = pack_bf16(oh[4] * inv, oh[5] * inv); v.w = pack_bf16(oh[6] * inv, oh[7] * inv);
+                    *reinterpret_cast<uint4*>(static_cast<uint16_t*>(a.out.O) + e) = v;
+                } else {
+                    float* op = static_cast<float*>(a.out.O) + e;
+                    *reinterpret_cast<float4*>(op) = make_float4(oh[0] * inv, oh[1] * inv, oh[2] * inv, oh[3] * inv);
+                    *reinterpret_cast<float4*>(op + 4) = make_float4(oh[4] * inv, oh[5] * inv, oh[6] * inv, oh[7] * inv);
+                }
             }
             if (lane == 0)
                 a.out.LSE[(int64_t)c * a.out.part_stride_L + idx] = l > 0.f ? (Ms + __log2f(l)) * kLn2 : -INFINITY;
