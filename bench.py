@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--paged", type=int, default=0, help="rows per page: the suffix cache is a page pool read through a page table (0 = packed rows, the default)")
     ap.add_argument("--fp8-kv", action="store_true", help="the suffix cache holds 8-bit E4M3 codes with one scale per tensor (hg_hydragen_attn_fp8); a variant, not the headline")
     ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
+    ap.add_argument("--nq", type=int, default=1, help="queries per sequence (App. B's num_queries: the last nq suffix tokens are queried at once); a variant, value then counts B * nq queries")
     ap.add_argument("--suffix-kernel", type=int, default=0, help="HG_OPT_SUFFIX_KERNEL: 0 automatic, 1 vector-ALU, 2 matrix-core")
     ap.add_argument("--graph", action="store_true", help="also time the fused call replayed from a captured HIP graph (reported as graph_ms_per_step; the headline stays the eager call)")
     ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
@@ -78,7 +79,8 @@ def main() -> int:
     hb.lib()  # fail loudly if the HIP library is missing
 
     t0 = time.time()
-    w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None)
+    variant = {"nq": args.nq} if args.nq > 1 else {}
+    w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None, **variant)
     dw = dev.to_device(w)
     torch.cuda.synchronize()
     print(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} levels={[int(l.K.shape[0]) for l in w.levels]} "
@@ -95,8 +97,8 @@ def main() -> int:
         ctx.set_option(hb.HG_OPT_WIDE_SLOTS, args.wide_slots)
     ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, args.suffix_kernel)
 
-    O = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.bfloat16, device="cuda:0")
-    L = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
+    O = torch.empty(dw.lead + (dw.D,), dtype=torch.bfloat16, device="cuda:0")
+    L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
 
     kv = None
     f8 = None          # packed 8-bit cache
@@ -187,7 +189,8 @@ def main() -> int:
 
     # ---- algorithmic work per launch --------------------------------------------------------------------------
     B, Hq, Hkv, D, G = w.B, w.Hq, w.Hkv, w.D, w.G
-    rows = B * Hq
+    nq = w.nq
+    rows = B * nq * Hq
     T = int(np.minimum(w.lengths, w.max_len).sum())
     kv_elem = 1 if args.fp8_kv else 2
     suffix_bytes = 2 * kv_elem * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
@@ -197,8 +200,8 @@ def main() -> int:
         for g in range(lv.Gn):
             nk = int(lv.kv_off[g + 1] - lv.kv_off[g])
             ns = int(lv.seq_off[g + 1] - lv.seq_off[g])
-            f += 4 * ns * Hq * nk * D
-            by += 4 * nk * Hkv * D + ns * Hq * D * 2 + ns * Hq * (D + 1) * 4
+            f += 4 * ns * nq * Hq * nk * D
+            by += 4 * nk * Hkv * D + ns * nq * Hq * D * 2 + ns * nq * Hq * (D + 1) * 4
         level_flops.append(f)
         level_bytes.append(by)
     kernels = {"suffix": {"bound": "hbm", "ms": suffix_ms, "achieved": suffix_bytes / (suffix_ms * 1e-3) / 1e9 if suffix_ms else 0.0,
@@ -292,7 +295,7 @@ def main() -> int:
                 K8, V8, off8 = oracle.paged_to_packed(pg8.K, pg8.V, pg8.table[seqs], pg8.page_size, w.lengths[seqs])
             Os, Ls = ofp8.suffix_attention_fp8(w.Q[seqs], Hkv, K8, V8, ks8, vs8, off8, w.lengths[seqs], w.scale)
             Oref, Lref = oracle.merge([Op, Os], [Lp, Ls])
-        cpu = {"value": len(seqs) / (c1 - c0), "unit": "queries/s per layer", "cores": oracle.num_threads(), "kind": "oracle",
+        cpu = {"value": len(seqs) * nq / (c1 - c0), "unit": "queries/s per layer", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"{len(seqs)} of {B} sequences (evenly spaced + shortest and longest suffix), all {Hq} heads, full key lists; "
                          f"{c1 - c0:.1f}s wall"}
         idx = torch.from_numpy(seqs.astype(np.int64)).cuda()
@@ -310,11 +313,11 @@ def main() -> int:
 
     out = {
         "metric": "decode-attn queries/s per layer (B=1024, 16K prefix); MFMA util + HBM GB/s",
-        "value": B / (ms_per_step * 1e-3),
+        "value": B * nq / (ms_per_step * 1e-3),
         "unit": "queries/s per layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D,
+        "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D, "queries_per_sequence": nq,
                    "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
                    "suffix_len": [int(w.lengths.min()), int(w.lengths.max())], "suffix_tokens": int(w.T), "seed": w.seed,
                    "overlap_streams": args.overlap, "suffix_cache": (f"paged, {args.paged} rows per page" if args.paged else "packed rows") + (", 8-bit E4M3 codes" if args.fp8_kv else "")},
@@ -325,7 +328,7 @@ def main() -> int:
                      "ms_per_step_serialised": serial_ms_per_step},
         "stage_ms_timed_region": {"suffix": float(st_timed[0]), "prefix_levels": [float(x) for x in st_timed[1:1 + nlev]],
                                   "merge": float(st_timed[1 + nlev]), "note": "kernels overlap: each span includes the other's work"},
-        "naive": None if naive_ms is None else {"ms_per_step": naive_ms, "queries_per_s": B / (naive_ms * 1e-3),
+        "naive": None if naive_ms is None else {"ms_per_step": naive_ms, "queries_per_s": B * nq / (naive_ms * 1e-3),
                                                  "speedup_hydragen_over_naive": naive_ms / ms_per_step},
         "kv_append_ms": append_ms,
         "graph_ms_per_step": graph_ms,
