@@ -33,6 +33,12 @@ MEASURED_TRAFFIC = {
     ("prefix_level0", "c4_gqa"): int((12480.9 / 0.50003 + 35728.4) * 1024),
     ("suffix", "c4_gqa"): int((276987.8 / 0.50003 + 16513.9) * 1024),
 }
+# Matrix-core busy fraction of the shared-block kernel from a rocprofv3 --pmc run of its own
+# (profiles/fused_c3_P16384_mfma_util.txt): SQ_VALU_MFMA_BUSY_CYCLES / (active cycles x 1024 SIMDs), and the clock
+# the kernel ran at (active cycles / duration); keyed like MEASURED_TRAFFIC.
+MEASURED_MFMA_UTIL = {
+    ("prefix_level0", "c3_long_P16384"): {"mfma_busy_frac_of_cycles": 0.596, "clock_ghz": 1.81},
+}
 
 
 def main() -> int:
@@ -225,6 +231,7 @@ def main() -> int:
     dom = kernels[dom_name]
     roofline = {"kernel": dom_name, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
                 "frac": dom["frac"], "traffic": MEASURED_TRAFFIC.get((dom_name, w.name)), "avg_launch_ms": dom["ms"],
+                "mfma_util": MEASURED_MFMA_UTIL.get((dom_name, w.name)),
                 "measured": "HIP events around the kernel on its stream, mean over the serialised pass of the same K steps"
                             if serial_ms_per_step is not None else "HIP events around the kernel on its stream, mean over the timed region"}
 
