@@ -136,7 +136,8 @@ int hg_prefix_attn_grouped(hg_ctx* ctx, const void* Q, const hg_level* level,
  * Per-sequence attention over ragged suffix KV (Sec. 3.2, last paragraph).  Sequence b owns rows
  * [offsets[b], offsets[b] + lengths[b]) of Ks/Vs (bf16 [T, Hkv, D]); offsets/lengths are DEVICE int32[B];
  * a padded [B, Lmax, Hkv, D] cache is offsets[b] = b * Lmax.  lengths[b] == 0 is legal; lengths above
- * max_len (a host upper bound) are truncated to max_len.  Rows of Ks/Vs that no sequence owns (padding, slots of
+ * max_len (a host upper bound) are truncated to max_len; max_len * Hkv * D must stay below 2^31 (else
+ * HG_ERR_UNSUPPORTED).  Rows of Ks/Vs that no sequence owns (padding, slots of
  * empty sequences) may hold anything, NaN included: they are never given a weight and never reach a result.
  */
 int hg_suffix_attn(hg_ctx* ctx, const void* Q, const void* Ks, const void* Vs,

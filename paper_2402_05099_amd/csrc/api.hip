@@ -67,6 +67,11 @@ int check_shape(int B, int Hq, int Hkv, int D, int nq) {
     return HG_OK;
 }
 
+// Byte offsets inside one sequence's suffix rows are 32-bit in the kernels: max_len * Hkv * D elements must stay below 2^31.
+int check_suffix_span(int max_len, int Hkv, int D) {
+    return (int64_t)max_len * Hkv * D >= (1LL << 31) ? HG_ERR_UNSUPPORTED : HG_OK;
+}
+
 int check_level(const hg_level* lv, int Hkv, int D) {
     if (!lv) return HG_ERR_INVALID_ARG;
     if (lv->n_blocks < 1 || lv->max_rows < 0 || lv->max_seqs < 0) return HG_ERR_INVALID_ARG;
@@ -476,6 +481,8 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (!c || !O || !LSE || (o_dtype != HG_F32 && o_dtype != HG_BF16) || max_len < 0) return HG_ERR_INVALID_ARG;
     int rc = check_shape(B, Hq, Hkv, D, c ? c->opt_nq : 1);
     if (rc) return rc;
+    rc = check_suffix_span(max_len, Hkv, D);
+    if (rc) return rc;
     if (B == 0) return HG_OK;
     if (!Q || (!offsets && !paged) || !lengths) return HG_ERR_INVALID_ARG;
     if (max_len > 0 && (!Ks || !Vs)) return HG_ERR_INVALID_ARG;
@@ -588,6 +595,10 @@ static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* l
     }
     if (B > 0 && !Q) return HG_ERR_INVALID_ARG;
     if (Ks && max_len > 0 && (!Vs || (!offsets && !paged) || !lengths)) return HG_ERR_INVALID_ARG;
+    if (Ks) {
+        rc = check_suffix_span(max_len, Hkv, D);
+        if (rc) return rc;
+    }
     return HG_OK;
 }
 

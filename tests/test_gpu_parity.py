@@ -349,6 +349,8 @@ def test_error_paths_launch_nothing():
     assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 64, -1, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
     assert lib.hg_prefix_attn(ctx.h, p(dw.Q), p(lv.K), p(lv.V), 4, 4, 4, 64, 128, 0.0, p(O), 9, p(L)) == hb.HG_ERR_INVALID_ARG
     assert lib.hg_suffix_attn(ctx.h, p(dw.Q), p(dw.Ks), p(dw.Vs), p(dw.offsets), p(dw.lengths), -5, 4, 4, 4, 64, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
+    # a suffix so long that 32-bit byte offsets inside one sequence's rows would overflow
+    assert lib.hg_suffix_attn(ctx.h, p(dw.Q), p(dw.Ks), p(dw.Vs), p(dw.offsets), p(dw.lengths), 1 << 23, 4, 4, 4, 64, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_UNSUPPORTED
     # fused call needs room for levels+1 partials: one part is not enough
     with pytest.raises(hb.HydragenError) as e:
         dev.hydragen(ctx, dw, torch.float32)
