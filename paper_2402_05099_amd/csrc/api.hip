@@ -186,14 +186,12 @@ bool auto_mfma(int nq, int G, int max_len) { return nq >= 2 || G >= 3 || (G == 2
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
 // max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30,
-                       bool fp8 = false) {
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30) {
     SuffixPlan p;
     p.gt = pick_gt(G);
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
-    (void)fp8;   // both kernels read either cache format
     p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len));
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
@@ -494,7 +492,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
@@ -636,7 +634,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         }
         // K and V, bf16 (or 8-bit codes; on the matrix cores their expansion costs about a third of the saving); the
         // vector-ALU kernel reads them once per query; mean length taken as 0.75 max_len
-        const bool sfx_mfma = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, 1 << 30, fmt.fp8 != 0).mfma;
+        const bool sfx_mfma = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr).mfma;
         const double per_elem = fmt.fp8 ? (sfx_mfma ? 2.6 : 2.0) : 4.0;
         const double bytes = per_elem * B * (sfx_mfma ? 1 : nq) * (0.75 * max_len) * Hkv * D;
         wide_slots = pick_wide_slots(flops, bytes, T);
@@ -652,7 +650,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         ++nlev;
     }
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
