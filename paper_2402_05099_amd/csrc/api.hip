@@ -173,7 +173,7 @@ struct SuffixPlan { int chunk, nchunks, gt; bool mfma; int ipw; };
 // Storage format of the suffix cache: bf16 rows, or E4M3 codes with one scale per tensor (value = code * scale).
 struct KvFmt { int fp8 = 0; float k_scale = 1.f, v_scale = 1.f; };
 
-// Automatic choice between the two per-sequence kernels for D = 128.  The matrix-core kernel reads every K/V row
+// Automatic choice between the two per-sequence kernels (thresholds measured at D = 128).  The matrix-core kernel reads every K/V row
 // once for all nq * G query rows that a KV head serves; the vector-ALU kernel pays one dot product per row and key
 // and, across queries, re-reads the suffix.  Measured (B = 512, lengths up to 512, matrix-core against vector-ALU):
 // nq = 2: 184 against 368 us; G = 3: 96 against 211 us; G = 2: 94 against 114 us, but 178 against 153 us when no
@@ -182,17 +182,19 @@ bool auto_mfma(int nq, int G, int max_len) { return nq >= 2 || G >= 3 || (G == 2
 
 // Work items of the suffix kernel are (sequence, query, KV head, group of query heads, key chunk), one wavefront
 // each, in the vector-ALU kernel, and (sequence, KV head, 32-row tile of the nq * G rows, key chunk) in the
-// matrix-core kernel (D = 128; chosen by auto_mfma, HG_OPT_SUFFIX_KERNEL forces either).
+// matrix-core kernel (chosen by auto_mfma, HG_OPT_SUFFIX_KERNEL forces either; an 8-bit cache at D = 64 stays on the
+// vector ALU).
 // 256 keys per chunk by default; when that leaves fewer than eight wavefronts per CU (few sequences or KV heads)
 // the chunks shrink, down to 64 keys, so that enough loads are in flight to cover HBM latency.
 // max_chunk bounds the keys per work item (a paged cache allows 32 pages per work item).
-SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30) {
+SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int Hkv, int D, bool paged, int max_chunk = 1 << 30,
+                       bool fp8 = false) {
     SuffixPlan p;
     p.gt = pick_gt(G);
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
-    p.mfma = D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len));
+    p.mfma = (D == 128 || !fp8) && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len));   // 8-bit rows on the matrix cores: D = 128 only
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
@@ -245,7 +247,7 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
         // consecutive items per wavefront: the copies of the next item are in flight while one is finished; few
         // enough per wavefront that the hardware still balances ragged lengths (>= 8 workgroups per resident slot)
         a.ipw = mfma_ipw > 0 ? mfma_ipw : (int)std::min<int64_t>(4, std::max<int64_t>(1, items / (1280 * 8)));
-        return hip_rc(launch_decode_mfma(a, s));
+        return hip_rc(launch_decode_mfma(a, D, s));
     }
     return hip_rc(launch_decode(a, D, gt, s));
 }
@@ -492,7 +494,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     const Parts parts = carve(c, rows, D);
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
+    SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
         p.nchunks = parts.cap > 1 ? parts.cap : 1;
         p.chunk = round_up(ceil_div(max_len, p.nchunks), 32);
@@ -634,7 +636,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         }
         // K and V, bf16 (or 8-bit codes; on the matrix cores their expansion costs about a third of the saving); the
         // vector-ALU kernel reads them once per query; mean length taken as 0.75 max_len
-        const bool sfx_mfma = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr).mfma;
+        const bool sfx_mfma = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, 1 << 30, fmt.fp8 != 0).mfma;
         const double per_elem = fmt.fp8 ? (sfx_mfma ? 2.6 : 2.0) : 4.0;
         const double bytes = per_elem * B * (sfx_mfma ? 1 : nq) * (0.75 * max_len) * Hkv * D;
         wide_slots = pick_wide_slots(flops, bytes, T);
@@ -650,7 +652,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         ++nlev;
     }
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
-    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk);
+    SuffixPlan sp = plan_suffix(c, max_len, G, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
     if (!has_suffix) sp.nchunks = 0;
     auto total_parts = [&]() { int t = sp.nchunks; for (int i = 0; i < nlev; ++i) t += ns[i]; return t; };
     if (nlev + (has_suffix ? 1 : 0) > parts.cap) return HG_ERR_WORKSPACE;
@@ -865,7 +867,7 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (parts.cap < 1) return HG_ERR_WORKSPACE;
     if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
     if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
-    if (D == 128 && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, (int)nmax))) {
+    if (c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, (int)nmax))) {
         // Several query rows per KV head: the per-sequence kernel on the matrix cores, once per level (every sequence
         // walks the block that covers it by itself) and once for the suffix, each writing its own partial results.
         int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 1024;

@@ -1,5 +1,5 @@
-// Suffix attention on the matrix cores (Sec. 3.2, last paragraph; App. B with num_queries >= 1), D = 128, packed
-// suffix rows.  The per-sequence part of Hydragen is a matrix-vector product only while one KV head serves one
+// Suffix attention on the matrix cores (Sec. 3.2, last paragraph; App. B with num_queries >= 1), D = 64 or 128, packed
+// or paged suffix rows.  The per-sequence part of Hydragen is a matrix-vector product only while one KV head serves one
 // query row; with grouped-query attention and with several queries per sequence a KV head serves R = nq * G rows,
 // and the vector-ALU kernel (decode.hip) then pays R dot products per key and, across queries, re-reads the
 // suffix.  Here a work item is (sequence, KV head, 32-row tile of the R rows, key chunk): every K/V row is read
@@ -33,16 +33,26 @@ namespace hg {
 
 namespace {
 
-constexpr int D = 128;
 constexpr int KT = 32;                  // keys per stage
-constexpr int KS = D / 16;              // MFMA k-steps of the score product
-constexpr int DB = D / 32;              // 32-row blocks of O^T
-constexpr int CPR = D / 8;              // 16-byte chunks per K/V row
-constexpr int RPI = 64 / CPR;           // rows one copy instruction covers
-constexpr int CPS = KT / RPI;           // copy instructions per stage and tensor
-constexpr int ROWB = D * 2;             // bytes per row
-constexpr int STB = KT * ROWB;          // bytes per stage and tensor
 constexpr float TAU = 8.0f;             // lazy-rescale threshold, log2 units
+
+// Sizes that follow from the head dimension, and the XOR swizzles of the 16-byte chunks of a bf16 row in LDS (applied
+// on the global side of the copies).  D = 128: a row is 256 bytes, one period of the 64 banks: K (and Q) chunk ^ row % 16
+// makes the 16 rows of a ds_read_b128 pass distinct, V chunk ^ 4 (row % 4) separates the 4 rows of a transposing read.
+// D = 64: a row is half a period, so consecutive rows already differ; K chunk ^ (row / 2) % 8, V chunk ^ 4 ((row / 2) % 2).
+template <int D>
+struct Geo {
+    static_assert(D == 64 || D == 128, "head dimension");
+    static constexpr int KS = D / 16;              // MFMA k-steps of the score product
+    static constexpr int DB = D / 32;              // 32-row blocks of O^T
+    static constexpr int CPR = D / 8;              // 16-byte chunks per bf16 row
+    static constexpr int RPI = 64 / CPR;           // rows one copy instruction covers
+    static constexpr int CPS = KT / RPI;           // copy instructions per stage and tensor
+    static constexpr int ROWB = D * 2;             // bytes per bf16 row
+    static constexpr int STB = KT * ROWB;          // bytes per stage and tensor
+    static __device__ __forceinline__ int kswz(int row) { return D == 128 ? row % 16 : (row >> 1) & 7; }
+    static __device__ __forceinline__ int vswz(int row) { return D == 128 ? 4 * (row % 4) : 4 * ((row >> 1) & 1); }
+};
 
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -68,10 +78,13 @@ __device__ __forceinline__ void wait_vm() {
 // lie in one page (pages hold a power of two >= 16 rows), so a copy still has one scalar base.
 // SEG: the key range of sequence b is the block of level a.lv[0] that covers b (the non-decomposed comparison walks
 // the shared blocks per sequence); every query of the sequence sees all of it.
-template <int NS, bool PAGED, bool SEG, bool FP8 = false>
+template <int D, int NS, bool PAGED, bool SEG, bool FP8 = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
+    using G_ = Geo<D>;
+    constexpr int KS = G_::KS, DB = G_::DB, CPR = G_::CPR, RPI = G_::RPI, CPS = G_::CPS, ROWB = G_::ROWB, STB = G_::STB;
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
     static_assert(!(FP8 && SEG), "shared levels are bf16");
+    static_assert(!FP8 || D == 128, "8-bit rows: D = 128 only");
     // bf16: ring slot n holds K (or Q) at n * STB and V at (NS + n) * STB.  FP8: ring slot n holds the K codes at
     // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot); the bf16 V stage that the second
     // product reads is the work stage at NS * STB.
@@ -190,10 +203,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     // ---- LDS fragment addresses (relative to the slot), as in prefix_wide.hip ------------------------------------------
     unsigned kaddr[KS], qaddr[KS];     // K fragments of a stage, Q fragments of a tile (bf16: the same addresses)
 #pragma unroll
-    for (int s = 0; s < KS; ++s) kaddr[s] = qaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ (lq % CPR)) * 16));
+    for (int s = 0; s < KS; ++s) kaddr[s] = qaddr[s] = (unsigned)(lq * ROWB + (((2 * s + hl) ^ G_::kswz(lq)) * 16));
     // FP8: the 8 codes of K row lq, columns 16 s + 8 hl .. +7: rows lie in copy order (row r at (r/8) KiB + (r%8) 128 B),
     // their 16-byte chunks XOR-swizzled by (r/2) % 8 on the global side so that 16 consecutive lanes hit 32 different banks
-    if (FP8) {
+    if constexpr (FP8) {
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             kaddr[s] = (unsigned)((lq >> 3) * 1024 + (lq & 7) * 128 + ((s ^ ((lq >> 1) & 7)) * 16) + 8 * hl);
@@ -202,7 +215,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     {
         const int i16 = l & 15, g1 = (l >> 4) & 1;
         const int keyq = 4 * hl + (i16 >> 2);
-        const int fv = 4 * (keyq % 4);
+        const int fv = G_::vswz(keyq);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int chunk = 4 * db + 2 * g1 + ((i16 & 3) >> 1);
@@ -242,8 +255,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                     voffK[i] = ro + (unsigned)((schg ^ ((srow >> 1) & 7)) * 16);
                     voffV[i] = ro + (unsigned)(schg * 16);
                 } else {
-                    voffK[i] = ro + (unsigned)((sch ^ (srow % CPR)) * 16);
-                    voffV[i] = ro + (unsigned)((sch ^ (4 * (srow % 4))) * 16);
+                    voffK[i] = ro + (unsigned)((sch ^ G_::kswz(srow)) * 16);
+                    voffV[i] = ro + (unsigned)((sch ^ G_::vswz(srow)) * 16);
                 }
             }
         }
@@ -254,7 +267,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 const int srow = i * RPI + lrow;
                 int r = pit.rt * 32 + srow;                 // Q tile row i is query row rt*32 + i of (b, kvh); row 0 when past R
                 if (r >= R) r = 0;
-                voffQ[i] = (unsigned)((r / a.G) * a.Hq + r % a.G) * ROWB + (unsigned)((sch ^ (srow % CPR)) * 16);
+                voffQ[i] = (unsigned)((r / a.G) * a.Hq + r % a.G) * ROWB + (unsigned)((sch ^ G_::kswz(srow)) * 16);
             }
         }
     };
@@ -431,7 +444,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                         w[2 * j + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
                     }
                     const int row = i * RPIG + lrowg;
-                    const int swz = 4 * (row % 4);
+                    const int swz = G_::vswz(row);
                     unsigned char* const rowp = vstage + row * ROWB;
                     *reinterpret_cast<uintx4*>(rowp + (((2 * schg) ^ swz) * 16)) = uintx4{w[0], w[1], w[2], w[3]};
                     *reinterpret_cast<uintx4*>(rowp + (((2 * schg + 1) ^ swz) * 16)) = uintx4{w[4], w[5], w[6], w[7]};
@@ -564,26 +577,38 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     }
 }
 
-// Work items: B * nchunks * ceil(nq*G / 32) * Hkv, adjacent ids on adjacent KV heads of the same rows; a.ipw
-// consecutive items per wavefront (= workgroup).
-hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s) {
-    constexpr int NS = 2;   // 32 KiB of LDS per wavefront, four wavefronts per CU (rings of 3 and 4 were slower)
-    if (a.items == 0) return hipSuccess;
-    if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
+template <int D>
+static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
+    constexpr int NS = 2;   // D = 128: 32 KiB of LDS per wavefront, four wavefronts per CU (rings of 3 and 4 were slower)
+    constexpr int STB = Geo<D>::STB;
     const int grid = (a.items + a.ipw - 1) / a.ipw;
-    if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
     if (a.fp8) {
-        if (a.seg) return hipErrorInvalidValue;
-        if (a.pg.table) decode_mfma_kernel<NS, true, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
-        else decode_mfma_kernel<NS, false, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
+        if constexpr (D == 128) {
+            if (a.seg) return hipErrorInvalidValue;
+            if (a.pg.table) decode_mfma_kernel<D, NS, true, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
+            else decode_mfma_kernel<D, NS, false, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
+        } else {
+            return hipErrorInvalidValue;   // 8-bit rows on the matrix cores: D = 128 only
+        }
     } else if (a.pg.table) {
-        decode_mfma_kernel<NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        decode_mfma_kernel<D, NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else if (a.seg) {
-        decode_mfma_kernel<NS, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        decode_mfma_kernel<D, NS, false, true><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else {
-        decode_mfma_kernel<NS, false, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        decode_mfma_kernel<D, NS, false, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     }
     return hipGetLastError();
+}
+
+// Work items: B * nchunks * ceil(nq*G / 32) * Hkv, adjacent ids on adjacent KV heads of the same rows; a.ipw
+// consecutive items per wavefront (= workgroup).
+hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s) {
+    if (a.items == 0) return hipSuccess;
+    if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
+    if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
+    if (D == 128) return launch_decode_mfma_t<128>(a, s);
+    if (D == 64) return launch_decode_mfma_t<64>(a, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace hg

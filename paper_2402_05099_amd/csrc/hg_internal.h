@@ -126,7 +126,7 @@ hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s);
 hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only; a.wide from plan_prefix_wide
 bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slots_per_xcd, WidePlan* out);
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
-hipError_t launch_decode_mfma(const DecodeArgs& a, hipStream_t s);   // D = 128, packed suffix rows, no shared levels
+hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s);   // matrix-core per-sequence kernel (8-bit rows: D = 128 only)
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);

@@ -93,7 +93,7 @@ def test_suffix_attn(idx, chunk):
 
 @pytest.mark.parametrize("kernel", [1, 2, 3, 4], ids=["valu", "mfma", "mfma_ipw3", "mfma_ipw1000"])
 @pytest.mark.parametrize("chunk", [0, 32, 96])
-@pytest.mark.parametrize("case", ["mha", "gqa8", "gqa4_nq3", "mha_nq5", "gqa8_nq7_two_row_tiles", "long"])
+@pytest.mark.parametrize("case", ["mha", "gqa8", "gqa4_nq3", "mha_nq5", "gqa8_nq7_two_row_tiles", "long", "d64_gqa8", "d64_mha_nq3", "d64_long"])
 def test_suffix_kernels(case, chunk, kernel):
     """Both suffix kernels (vector-ALU, matrix-core) on every shape class: one row per KV head, grouped heads, several
     queries per sequence (causal tail, suffixes shorter than the query block), more than 32 rows per KV head, and
@@ -114,6 +114,12 @@ def test_suffix_kernels(case, chunk, kernel):
         w = wl.make_workload(case, 84, 17, 4, 4, 128, [], 0, 0, lengths=lens(17, 100, 5), nq=5)
     elif case == "gqa8_nq7_two_row_tiles":   # 56 rows per KV head: two 32-row tiles, the second half empty
         w = wl.make_workload(case, 85, 11, 8, 1, 128, [], 0, 0, lengths=lens(11, 90, 7), nq=7)
+    elif case == "d64_gqa8":                 # head dimension 64: 128-byte rows, other swizzles, half as many k-steps
+        w = wl.make_workload(case, 87, 23, 16, 2, 64, [], 0, 0, lengths=lens(23, 200, 1))
+    elif case == "d64_mha_nq3":
+        w = wl.make_workload(case, 88, 19, 3, 3, 64, [], 0, 0, lengths=lens(19, 130, 3), nq=3)
+    elif case == "d64_long":
+        w = wl.make_workload(case, 89, 9, 8, 2, 64, [], 0, 0, lengths=lens(9, 700, 1))
     else:
         w = wl.make_workload(case, 86, 9, 8, 2, 128, [], 0, 0, lengths=lens(9, 700, 1))
     dw = dev.to_device(w)
