@@ -43,7 +43,7 @@ def random_workload(seed: int) -> wl.Workload:
     return w
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(40))
 def test_random_shape(seed):
     w = random_workload(seed)
     rng = np.random.default_rng(5000 + seed)
