@@ -177,8 +177,14 @@ struct KvFmt { int fp8 = 0; float k_scale = 1.f, v_scale = 1.f; };
 // once for all nq * G query rows that a KV head serves; the vector-ALU kernel pays one dot product per row and key
 // and, across queries, re-reads the suffix.  Measured (B = 512, lengths up to 512, matrix-core against vector-ALU):
 // nq = 2: 184 against 368 us; G = 3: 96 against 211 us; G = 2: 94 against 114 us, but 178 against 153 us when no
-// sequence has more than 128 rows (the per-item cost of the matrix-core kernel); one row: the vector-ALU kernel.
-bool auto_mfma(int nq, int G, int max_len) { return nq >= 2 || G >= 3 || (G == 2 && max_len >= 256); }
+// sequence has more than 128 rows (the per-item cost of the matrix-core kernel).  One row per KV head: the
+// matrix-core kernel streams long rows better (6.4 against 5.8-6.0 TB/s from a few hundred rows per sequence on:
+// lengths 64..384: 794 against 841 us; 256..1024: 824 against 915 us) and loses on short ones (lengths up to 256:
+// 121 against 116 us; 32..128: 328 against 285 us).  At D = 64 that last gain is not consistent (402 against 440 us at
+// 64..384 rows, 462 against 427 us at 1024..4096) and the clause is left out.
+bool auto_mfma(int nq, int G, int max_len, int D) {
+    return nq >= 2 || G >= 3 || (G == 2 && max_len >= 256) || (D == 128 && max_len >= 384);
+}
 
 // Work items of the suffix kernel are (sequence, query, KV head, group of query heads, key chunk), one wavefront
 // each, in the vector-ALU kernel, and (sequence, KV head, 32-row tile of the nq * G rows, key chunk) in the
@@ -194,7 +200,7 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
     const int R = nq * G;
     p.ipw = c->opt_suffix_ipw;
     (void)paged;
-    p.mfma = (D == 128 || !fp8) && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len));   // 8-bit rows on the matrix cores: D = 128 only
+    p.mfma = (D == 128 || !fp8) && c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, max_len, D));   // 8-bit rows on the matrix cores: D = 128 only
     if (p.mfma) max_chunk = 1 << 30;   // the matrix-core kernel looks pages up per stage: no limit on pages per item
     if (c->opt_suffix_chunk > 0) {
         p.chunk = round_up(c->opt_suffix_chunk, 32);
@@ -867,7 +873,8 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     if (parts.cap < 1) return HG_ERR_WORKSPACE;
     if (nmax == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
     if (nmax >= (1LL << 30)) return HG_ERR_UNSUPPORTED;
-    if (c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || auto_mfma(nq, G, (int)nmax))) {
+    // (with one row per KV head the vector-ALU kernel is the faster comparison: 38 against 49 ms on config 3)
+    if (c->opt_suffix_kernel != 1 && (c->opt_suffix_kernel == 2 || (nq * G >= 2 && auto_mfma(nq, G, (int)nmax, D)))) {
         // Several query rows per KV head: the per-sequence kernel on the matrix cores, once per level (every sequence
         // walks the block that covers it by itself) and once for the suffix, each writing its own partial results.
         int chunk = c->opt_naive_chunk > 0 ? round_up(c->opt_naive_chunk, 32) : 1024;

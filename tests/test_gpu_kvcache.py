@@ -259,7 +259,9 @@ def test_paged_error_paths_launch_nothing():
     assert lib.hg_suffix_attn_paged(ctx.h, dw.Q.data_ptr(), None, dw.lengths.data_ptr(), dw.max_len, dw.B, dw.Hq, dw.Hkv, dw.D,
                                     0.0, O.data_ptr(), hb.HG_F32, L.data_ptr()) == hb.HG_ERR_INVALID_ARG
     # one partial result cannot cover more than 32 pages: max_len 4096 over 16-row pages needs 8
+    # (a limit of the vector-ALU kernel, which such long suffixes get only on request)
     small = hb.Context(0, hb.hg_workspace_bytes(dw.B, dw.Hq, dw.D, 2))
+    small.set_option(hb.HG_OPT_SUFFIX_KERNEL, 1)
     st = kv.c_struct(); st.table_stride = 256
     assert call(st, max_len=4096, c=small) == hb.HG_ERR_WORKSPACE
     torch.cuda.synchronize()

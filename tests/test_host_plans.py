@@ -74,7 +74,8 @@ def test_wide_plan_rejects_what_it_cannot_run():
     (1024, 1, 40, 40, 128, 128, 0), (512, 1, 64, 8, 128, 512, 0), (512, 1, 64, 8, 128, 512, 16), (4, 1, 4, 4, 64, 16, 0),
     (1024, 4, 40, 40, 128, 128, 0), (2048, 1, 40, 40, 128, 64, 0), (3, 1, 8, 1, 128, 5000, 0), (256, 1, 40, 40, 128, 4096, 16),
     (1, 1, 1, 1, 64, 1, 0), (7, 6, 8, 2, 64, 300, 32), (512, 2, 16, 16, 128, 512, 0), (512, 1, 24, 8, 128, 100, 0),
-    (512, 1, 16, 8, 128, 512, 0), (512, 1, 16, 8, 128, 128, 0), (512, 1, 16, 8, 128, 256, 16),
+    (512, 1, 16, 8, 128, 512, 0), (512, 1, 16, 8, 128, 128, 0), (512, 1, 16, 8, 128, 256, 16), (64, 1, 32, 32, 128, 383, 0),
+    (64, 1, 32, 32, 128, 384, 0),
 ])
 def test_suffix_plan_limits(B, nq, Hq, Hkv, D, max_len, ps):
     p = hb.hg_debug_suffix_plan(B, nq, Hq, Hkv, D, max_len, ps)
@@ -82,7 +83,7 @@ def test_suffix_plan_limits(B, nq, Hq, Hkv, D, max_len, ps):
     assert p["chunk"] % 32 == 0 and p["chunk"] >= 32
     assert p["nchunks"] * p["chunk"] >= max_len and (p["nchunks"] - 1) * p["chunk"] < max(max_len, 1)
     G = Hq // Hkv
-    several = nq >= 2 or G >= 3 or (G == 2 and max_len >= 256)
+    several = nq >= 2 or G >= 3 or (G == 2 and max_len >= 256) or (D == 128 and max_len >= 384)   # ... or long rows to stream
     assert p["mfma"] == int(several), "matrix cores when a KV head serves several rows of a sequence"
     assert G % p["gt"] == 0 and p["gt"] in (1, 2, 4, 8)
     if ps and not p["mfma"]:
