@@ -19,11 +19,10 @@
 // suffix rows [0, length - (nq-1-t)), applied as a per-lane bound on the key index in the stages that reach it.
 //
 // FP8: the suffix rows are 8-bit E4M3 codes (one fp32 scale per tensor; not in the paper).  A K/V ring element is then
-// 4 KiB + 4 KiB of codes (half the copy instructions).  K fragments are read as 8 bytes of codes and expanded in
-// registers (v_cvt_scalef32_pk_bf16_fp8, exact: every E4M3 value is a bf16 value); the V codes of a stage are
-// expanded into one bf16 work stage in LDS with the layout the transposing reads expect.  Products, masks and
-// softmax are the same code.  The K scale multiplies the softmax scale, the V scale the final normalisation.
-// 24 KiB of LDS per wavefront (2 x 8 KiB ring + 8 KiB work stage).
+// 4 KiB + 4 KiB of codes (half the copy instructions).  Fragments are read as 8 bytes of codes and expanded in
+// registers (v_cvt_scalef32_pk_bf16_fp8, exact: every E4M3 value is a bf16 value): K rows directly, V^T through
+// ds_read_b64_tr_b8, the 8-bit transposing read.  Products, masks and softmax are the same code.  The K scale
+// multiplies the softmax scale, the V scale the final normalisation.  16 KiB of LDS per wavefront (the ring alone).
 #include "hg_internal.h"
 #include "prefix_common.h"
 
@@ -86,8 +85,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     static_assert(!(FP8 && SEG), "shared levels are bf16");
     static_assert(!FP8 || D == 128, "8-bit rows: D = 128 only");
     // bf16: ring slot n holds K (or Q) at n * STB and V at (NS + n) * STB.  FP8: ring slot n holds the K codes at
-    // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot); the bf16 V stage that the second
-    // product reads is the work stage at NS * STB.
+    // n * STB and the V codes at n * STB + STB / 2 (a Q element fills the slot).
     constexpr int ES = FP8 ? 1 : 2;                // bytes per cache element
     constexpr int CPRG = D * ES / 16;              // 16-byte chunks per cache row
     constexpr int RPIG = 64 / CPRG;                // cache rows one copy instruction covers
@@ -211,6 +209,22 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         for (int s = 0; s < KS; ++s)
             kaddr[s] = (unsigned)((lq >> 3) * 1024 + (lq & 7) * 128 + ((s ^ ((lq >> 1) & 7)) * 16) + 8 * hl);
     }
+    // FP8, V^T: ds_read_b64_tr_b8 works on groups of 16 lanes: every lane supplies the address of 8 bytes, and lane i
+    // of the group receives, as byte j, byte i % 8 of the piece that lane 2 j + i / 8 of the group pointed at.  So
+    // lane s of a group points at the V codes of key 8 (j / 4) + 4 hl + j % 4 (j = s / 2, the key of k-slot j), columns
+    // 16 g1 + 8 (s % 2) .. +7 of the 32-column block: lane i then holds column 16 g1 + i of the 8 keys in k-slot order.
+    // Rows lie in copy order (row r at (r / 8) KiB + (r % 8) 128 B); 16-byte chunks are XOR-swizzled on the global
+    // side by (r / 2) % 2 + 2 ((r / 8) % 2), which spreads the 8 rows of a read over all banks.
+    unsigned vaddr8[DB];
+    if constexpr (FP8) {
+        const int sg = l & 15, g1 = (l >> 4) & 1;
+        const int j = sg >> 1, pp = sg & 1;
+        const int row = 8 * (j >> 2) + 4 * hl + (j & 3);        // + 16 tt
+        const int fsw = ((row >> 1) & 1) | (((row >> 3) & 1) << 1);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            vaddr8[db] = (unsigned)((row >> 3) * 1024 + (row & 7) * 128 + (((2 * db + g1) ^ fsw) * 16) + 8 * pp);
+    }
     unsigned vaddr[DB];
     {
         const int i16 = l & 15, g1 = (l >> 4) & 1;
@@ -249,11 +263,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 const int srow = i * RPIG + lrowg;
                 const unsigned ro = (unsigned)min(srow, rowclamp) * rstride_b;
                 if (FP8) {
-                    // codes land in copy order (lane l of copy i holds row 8i + l/8): K chunks swizzled for the fragment
-                    // reads; V chunks as they are, the expansion reads them back lane by lane and applies the V
-                    // swizzle when it writes the bf16 work stage
+                    // codes land in copy order (lane l of copy i holds row 8i + l/8), chunks swizzled for the fragment reads
                     voffK[i] = ro + (unsigned)((schg ^ ((srow >> 1) & 7)) * 16);
-                    voffV[i] = ro + (unsigned)(schg * 16);
+                    voffV[i] = ro + (unsigned)((schg ^ (((srow >> 1) & 1) | (((srow >> 3) & 1) << 1))) * 16);
                 } else {
                     voffK[i] = ro + (unsigned)((sch ^ G_::kswz(srow)) * 16);
                     voffV[i] = ro + (unsigned)((sch ^ G_::vswz(srow)) * 16);
@@ -430,26 +442,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         } else {
             pending -= KVOPS;
             wait_for(pending);
-            unsigned char* const vstage = smem + (FP8 ? NS * STB : (sb - smem) + NS * STB);   // the bf16 V stage of this element
-            if constexpr (FP8) {
-                // expand the V codes of this element into the bf16 work stage: lane l of copy i holds row 8i + l/8,
-                // columns 16 (l%8) .. +15, i.e. the two 16-byte chunks 2 (l%8) and 2 (l%8) + 1 of the bf16 row
-#pragma unroll
-                for (int i = 0; i < CPSG; ++i) {
-                    const uintx4 raw = *reinterpret_cast<const uintx4*>(sb + VSLOT + i * 1024 + l * 16);
-                    unsigned w[8];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        w[2 * j] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, false));
-                        w[2 * j + 1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
-                    }
-                    const int row = i * RPIG + lrowg;
-                    const int swz = G_::vswz(row);
-                    unsigned char* const rowp = vstage + row * ROWB;
-                    *reinterpret_cast<uintx4*>(rowp + (((2 * schg) ^ swz) * 16)) = uintx4{w[0], w[1], w[2], w[3]};
-                    *reinterpret_cast<uintx4*>(rowp + (((2 * schg + 1) ^ swz) * 16)) = uintx4{w[4], w[5], w[6], w[7]};
-                }
-            }
+            unsigned char* const vstage = smem + (sb - smem) + VSLOT;   // the V part of this element
             // S^T = K Q^T
             floatx16 S;
 #pragma unroll
@@ -486,10 +479,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // in LDS, since their zero probabilities would still turn a NaN into a NaN in the second product
                 const int nhi = cit.ke - key0;
                 unsigned char* const vs = vstage;
+                if constexpr (FP8) {   // codes in copy order: lane l of copy i holds row 8i + l/8; code 0 is 0.0
 #pragma unroll
-                for (int i = 0; i < CPS; ++i) {
-                    const int row = i * RPI + lrow;
-                    if (row >= nhi) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                    for (int i = 0; i < CPSG; ++i)
+                        if (i * RPIG + lrowg >= nhi) *reinterpret_cast<uintx4*>(vs + i * 1024 + l * 16) = uintx4{0u, 0u, 0u, 0u};
+                } else {
+#pragma unroll
+                    for (int i = 0; i < CPS; ++i) {
+                        const int row = i * RPI + lrow;
+                        if (row >= nhi) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                    }
                 }
             }
             if (k0c != key0) {
@@ -498,10 +497,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 // zero, but 0 * NaN is NaN in the second product: clear those V rows in LDS.
                 const int nlo = key0 - k0c;
                 unsigned char* const vs = vstage;
+                if constexpr (FP8) {
 #pragma unroll
-                for (int i = 0; i < CPS; ++i) {
-                    const int row = i * RPI + lrow;
-                    if (row < nlo) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                    for (int i = 0; i < CPSG; ++i)
+                        if (i * RPIG + lrowg < nlo) *reinterpret_cast<uintx4*>(vs + i * 1024 + l * 16) = uintx4{0u, 0u, 0u, 0u};
+                } else {
+#pragma unroll
+                    for (int i = 0; i < CPS; ++i) {
+                        const int row = i * RPI + lrow;
+                        if (row < nlo) *reinterpret_cast<uintx4*>(vs + row * ROWB + sch * 16) = uintx4{0u, 0u, 0u, 0u};
+                    }
                 }
             }
             float tmax = fmaxf(S[0], S[1]);
@@ -537,11 +542,23 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const unsigned char* vp = vstage + vaddr[db] + tt * 16 * ROWB;
-                    const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
-                    const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
-                    const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                    if constexpr (FP8) {
+                        typedef int intx2 __attribute__((ext_vector_type(2)));
+                        const unsigned char* vp = vstage + vaddr8[db] + tt * 2048;     // keys 16 tt ..: two copy blocks further
+                        const intx2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) intx2*)HG_LDS(vp));
+                        uintx4 vv;
+                        vv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, false));
+                        vv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, true));
+                        vv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, false));
+                        vv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, true));
+                        Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                    } else {
+                        const unsigned char* vp = vstage + vaddr[db] + tt * 16 * ROWB;
+                        const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                        const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
+                        const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                    }
                 }
             }
             // the accumulators depend on every fragment read of this step: once they are pinned here the reads have
@@ -585,8 +602,8 @@ static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
     if (a.fp8) {
         if constexpr (D == 128) {
             if (a.seg) return hipErrorInvalidValue;
-            if (a.pg.table) decode_mfma_kernel<D, NS, true, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
-            else decode_mfma_kernel<D, NS, false, false, true><<<(unsigned)grid, 64, (NS + 1) * STB, s>>>(a);
+            if (a.pg.table) decode_mfma_kernel<D, NS, true, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+            else decode_mfma_kernel<D, NS, false, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
         } else {
             return hipErrorInvalidValue;   // 8-bit rows on the matrix cores: D = 128 only
         }
