@@ -22,6 +22,7 @@ HG_OPT_NUM_QUERIES = 8
 HG_KV_BF16, HG_KV_E4M3 = 0, 1
 HG_OPT_SUFFIX_KERNEL = 9
 HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10
+HG_OPT_SUFFIX_TILE_ROWS = 11
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)

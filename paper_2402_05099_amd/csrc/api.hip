@@ -20,6 +20,7 @@ struct hg_ctx {
     int opt_nq;            // queries per sequence (1 = decode)
     int opt_suffix_kernel; // 0 automatic, 1 vector-ALU kernel, 2 matrix-core kernel wherever it applies
     int opt_suffix_ipw;    // matrix-core suffix kernel: work items per wavefront (0 automatic)
+    int opt_suffix_tile;   // matrix-core suffix kernel: query rows per tile (0 automatic, 16, 32)
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -224,7 +225,7 @@ SuffixPlan plan_suffix(const hg_ctx* c, int max_len, int G, int B, int nq, int H
 int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, const void* Vs, const int32_t* offsets,
                const int32_t* lengths, int max_len, int B, int nq, int Hq, int Hkv, int D, float scale, int chunk, int nchunks,
                int gt, const OutDev& out, hipStream_t s, const PagedDev& pg = PagedDev{}, bool mfma = false, int mfma_ipw = 0, bool seg = false,
-               const KvFmt& fmt = KvFmt{}) {
+               const KvFmt& fmt = KvFmt{}, int mfma_tile = 0) {
     DecodeArgs a{};
     a.pg = pg;
     a.fp8 = fmt.fp8;
@@ -247,7 +248,9 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
     a.out = out;
     if (mfma) {
         a.seg = seg ? 1 : 0;
-        const int64_t items = (int64_t)B * nchunks * ceil_div(nq * a.G, 32) * Hkv;
+        // up to 16 rows per KV head and sequence fit a 16-row tile: half the matrix and softmax work per stage
+        a.tile_rows = (nq * a.G <= 16 && !fmt.fp8 && mfma_tile != 32) ? 16 : 32;
+        const int64_t items = (int64_t)B * nchunks * ceil_div(nq * a.G, a.tile_rows) * Hkv;
         if (items >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
         a.items = (int)items;
         // consecutive items per wavefront: the copies of the next item are in flight while one is finished; few
@@ -348,6 +351,7 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->opt_nq = 1;
     c->opt_suffix_kernel = 0;
     c->opt_suffix_ipw = 0;
+    c->opt_suffix_tile = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -409,6 +413,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_SUFFIX_ITEMS_PER_WAVE:
             if (value > 1024) return HG_ERR_INVALID_ARG;
             c->opt_suffix_ipw = value;
+            return HG_OK;
+        case HG_OPT_SUFFIX_TILE_ROWS:
+            if (value != 0 && value != 16 && value != 32) return HG_ERR_INVALID_ARG;
+            c->opt_suffix_tile = value;
             return HG_OK;
         case HG_OPT_WIDE_SLOTS:
             if (value > 32) return HG_ERR_INVALID_ARG;
@@ -509,9 +517,9 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     if (!p.mfma && p.chunk > max_chunk) return HG_ERR_WORKSPACE;
     if (p.nchunks == 1)
         return run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, 1, p.gt,
-                          direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw, false, fmt);
+                          direct_out(O, o_dtype, LSE), s, pg, p.mfma, p.ipw, false, fmt, c->opt_suffix_tile);
     rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, p.chunk, p.nchunks, p.gt,
-                    parts_out(parts, 0), s, pg, p.mfma, p.ipw, false, fmt);
+                    parts_out(parts, 0), s, pg, p.mfma, p.ipw, false, fmt, c->opt_suffix_tile);
     if (rc) return rc;
     return run_merge(p.nchunks, parts, 0, D, O, o_dtype, LSE, s);
 }
@@ -718,7 +726,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         if (!has_suffix) return HG_OK;
         if (!mark(0, 0, ssfx)) return HG_ERR_HIP;
         const int r = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, sp.chunk,
-                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg, sp.mfma, sp.ipw, false, fmt);
+                                 sp.nchunks, sp.gt, parts_out(parts, suffix_first), ssfx, pg, sp.mfma, sp.ipw, false, fmt, c->opt_suffix_tile);
         if (r) return r;
         if (!mark(0, 1, ssfx)) return HG_ERR_HIP;
         if (overlap && hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HG_ERR_HIP;
@@ -891,14 +899,14 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
             if (lv[i].max_rows <= 0) continue;
             const int n = ceil_div(lv[i].max_rows, chunk);
             rc = run_decode(Q, 1, &lv[i], lv[i].K, lv[i].V, nullptr, nullptr, lv[i].max_rows, B, nq, Hq, Hkv, D, scale, chunk, n, 1,
-                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, true);
+                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, true, KvFmt{}, c->opt_suffix_tile);
             if (rc) return rc;
             first += n;
         }
         if (has_suffix) {
             const int n = ceil_div(max_len, chunk);
             rc = run_decode(Q, 0, nullptr, Ks, Vs, offsets, lengths, max_len, B, nq, Hq, Hkv, D, scale, chunk, n, 1,
-                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, false);
+                            parts_out(parts, first), s, PagedDev{}, true, c->opt_suffix_ipw, false, KvFmt{}, c->opt_suffix_tile);
             if (rc) return rc;
             first += n;
         }

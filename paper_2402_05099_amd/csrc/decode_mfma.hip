@@ -77,8 +77,12 @@ __device__ __forceinline__ void wait_vm() {
 // lie in one page (pages hold a power of two >= 16 rows), so a copy still has one scalar base.
 // SEG: the key range of sequence b is the block of level a.lv[0] that covers b (the non-decomposed comparison walks
 // the shared blocks per sequence); every query of the sequence sees all of it.
-template <int D, int NS, bool PAGED, bool SEG, bool FP8 = false>
+// TR: query rows per tile.  32: v_mfma_f32_32x32x16_bf16, a lane owns row l % 32 and half of a stage's keys.  16 (when a
+// KV head serves at most 16 rows of a sequence, bf16 rows): v_mfma_f32_16x16x32_bf16, a lane owns row l % 16 and a
+// quarter of the keys; half the matrix work, half the softmax arithmetic and half the registers per stage.
+template <int D, int NS, bool PAGED, bool SEG, bool FP8 = false, int TR = 32>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
+    static_assert(TR == 32 || (TR == 16 && !FP8), "16-row tiles: bf16 rows only");
     using G_ = Geo<D>;
     constexpr int KS = G_::KS, DB = G_::DB, CPR = G_::CPR, RPI = G_::RPI, CPS = G_::CPS, ROWB = G_::ROWB, STB = G_::STB;
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
@@ -90,12 +94,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     constexpr int CPRG = D * ES / 16;              // 16-byte chunks per cache row
     constexpr int RPIG = 64 / CPRG;                // cache rows one copy instruction covers
     constexpr int CPSG = KT / RPIG;                // copy instructions per stage and tensor
-    constexpr int QOPS = CPS, KVOPS = 2 * CPSG;    // copy instructions per ring element
+    constexpr int QOPS = TR / RPI, KVOPS = 2 * CPSG;    // copy instructions per ring element
     constexpr int VSLOT = FP8 ? STB / 2 : NS * STB;   // from a ring element's K part to its V part
     unsigned char* const smem = dm_smem;
     const int l = threadIdx.x, lq = l & 31, hl = l >> 5;
+    const int ln = l & 15, lg = l >> 4;            // 16-row tiles: row of the tile and lane group (quarter of the keys)
+    const int lrw = TR == 16 ? ln : lq;            // this lane's row of the tile
     const int R = a.nq * a.G;
-    const int RT = (R + 31) >> 5;
+    const int RT = (R + TR - 1) / TR;
     const int item0 = blockIdx.x * a.ipw;
     const int item1 = min(item0 + a.ipw, a.items);
 
@@ -209,6 +215,26 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         for (int s = 0; s < KS; ++s)
             kaddr[s] = (unsigned)((lq >> 3) * 1024 + (lq & 7) * 128 + ((s ^ ((lq >> 1) & 7)) * 16) + 8 * hl);
     }
+    // 16-row tiles.  K (A operand, 16 keys x 32 columns per MFMA) and Q (B operand, 32 columns x 16 rows): lane (lg, ln)
+    // holds row ln of the 16-key group (of the tile), columns 32 s + 8 lg .. +7: 16-byte chunk 4 s + lg of that row.
+    // V^T (A operand, 16 columns x 32 keys): k-slot e of lane group lg stands for key 16 (e / 4) + 4 lg + e % 4, the key
+    // whose score this lane holds as element e % 4 of score tile e / 4; lane s of a group points ds_read_b64_tr_b16 at
+    // key 4 lg + s / 4, columns 16 db + 4 (s % 4) .. +3, and receives column 16 db + s of the group's four keys.
+    constexpr int KS16 = D / 32, DB16 = D / 16;
+    unsigned kaddr16[2][KS16], qaddr16[KS16], vaddr16[DB16];
+    if constexpr (TR == 16) {
+#pragma unroll
+        for (int s = 0; s < KS16; ++s) {
+            qaddr16[s] = (unsigned)(ln * ROWB + (((4 * s + lg) ^ G_::kswz(ln)) * 16));
+#pragma unroll
+            for (int kg = 0; kg < 2; ++kg)
+                kaddr16[kg][s] = (unsigned)((16 * kg + ln) * ROWB + (((4 * s + lg) ^ G_::kswz(16 * kg + ln)) * 16));
+        }
+        const int vrow = 4 * lg + (ln >> 2), q4 = ln & 3;
+#pragma unroll
+        for (int db = 0; db < DB16; ++db)
+            vaddr16[db] = (unsigned)(vrow * ROWB + (((2 * db + (q4 >> 1)) ^ G_::vswz(vrow)) * 16) + (q4 & 1) * 8);
+    }
     // FP8, V^T: ds_read_b64_tr_b8 works on groups of 16 lanes: every lane supplies the address of 8 bytes, and lane i
     // of the group receives, as byte j, byte i % 8 of the piece that lane 2 j + i / 8 of the group pointed at.  So
     // lane s of a group points at the V codes of key 8 (j / 4) + 4 hl + j % 4 (j = s / 2, the key of k-slot j), columns
@@ -275,9 +301,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         if (pit.rt != voff_rt) {
             voff_rt = pit.rt;
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) {
+            for (int i = 0; i < QOPS; ++i) {
                 const int srow = i * RPI + lrow;
-                int r = pit.rt * 32 + srow;                 // Q tile row i is query row rt*32 + i of (b, kvh); row 0 when past R
+                int r = pit.rt * TR + srow;                 // Q tile row i is query row rt*TR + i of (b, kvh); row 0 when past R
                 if (r >= R) r = 0;
                 voffQ[i] = (unsigned)((r / a.G) * a.Hq + r % a.G) * ROWB + (unsigned)((sch ^ G_::kswz(srow)) * 16);
             }
@@ -293,7 +319,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         if (p_el < 0) {
             const unsigned char* const qg = scalar_ptr(reinterpret_cast<const unsigned char*>(a.Q + ((int64_t)pit.b * a.nq * a.Hq + pit.kvh * a.G) * D));
 #pragma unroll
-            for (int i = 0; i < CPS; ++i) copy16(qg, voffQ[i], dst + i * (RPI * ROWB));
+            for (int i = 0; i < QOPS; ++i) copy16(qg, voffQ[i], dst + i * (RPI * ROWB));
             pending += QOPS;
         } else if (PAGED) {
             // logical rows r0 .. r0+31 of the sequence: copy i takes rows r0 + 4i .. +3, all in one page
@@ -334,16 +360,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             p_load(false);
         }
     };
-    // wait until at most `younger` copy instructions are outstanding (a multiple of CPS, at most (NS-1) * KVOPS)
+    // wait until at most `younger` copy instructions are outstanding (at most (NS-1) * KVOPS; more than six units: all)
     auto wait_for = [&](int younger) {
-        switch (younger / CPS) {
+        constexpr int WU = QOPS < KVOPS ? QOPS : KVOPS;   // every element is a multiple of this many copies
+        switch (younger / WU) {
             case 0: wait_vm<0>(); break;
-            case 1: wait_vm<1 * CPS>(); break;
-            case 2: wait_vm<2 * CPS>(); break;
-            case 3: wait_vm<3 * CPS>(); break;
-            case 4: wait_vm<4 * CPS>(); break;
-            case 5: wait_vm<5 * CPS>(); break;
-            case 6: wait_vm<6 * CPS>(); break;
+            case 1: wait_vm<1 * WU>(); break;
+            case 2: wait_vm<2 * WU>(); break;
+            case 3: wait_vm<3 * WU>(); break;
+            case 4: wait_vm<4 * WU>(); break;
+            case 5: wait_vm<5 * WU>(); break;
+            case 6: wait_vm<6 * WU>(); break;
             default: wait_vm<0>(); break;
         }
         asm volatile("" ::: "memory");
@@ -364,6 +391,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     int vis_end = 0, causal_from = 0;
     bf16x8 qf[KS];
     floatx16 Oacc[DB];
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    bf16x8 qf16[KS16];          // 16-row tiles
+    floatx4 Oacc16[DB16];
     float m_used = -INFINITY;   // raw-score maximum the exponentials are taken against (-inf: no key seen yet)
     float mc = 0.f;             // m_used * c2, 0 while no key has been seen
     float lsum = 0.f;           // this lane's share of the row sum (unrounded exponentials)
@@ -373,12 +403,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     for (int i = 0; i < DB; ++i)
 #pragma unroll
         for (int k = 0; k < 16; ++k) Oacc[i][k] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS16; ++s) qf16[s] = __builtin_bit_cast(bf16x8, uintx4{0, 0, 0, 0});
+#pragma unroll
+    for (int i = 0; i < DB16; ++i) Oacc16[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     int lane_rt = -1, lane_tq = 0, lane_g = 0;   // (query, head in the group) of this lane's row, for row tile lane_rt
     auto lane_of = [&](const Item& it) {
         if (it.rt != lane_rt) {
             lane_rt = it.rt;
-            const int r = it.rt * 32 + lq;    // this lane's row among the R rows of (b, kvh)
+            const int r = it.rt * TR + lrw;   // this lane's row among the R rows of (b, kvh)
             rv = r < R;
             const int rr = rv ? r : 0;
             lane_tq = rr / a.G;
@@ -400,13 +434,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             if (rv) {
                 float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
                 uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                constexpr int LPRW = 64 / TR;     // lanes that share a row: each writes every LPRW-th group of 4 columns
+                const int lsub = TR == 16 ? lg : hl;
 #pragma unroll
-                for (int i = 0; i < D / 8; ++i) {
-                    const int d = 8 * i + 4 * hl;
+                for (int i = 0; i < D / (4 * LPRW); ++i) {
+                    const int d = 4 * LPRW * i + 4 * lsub;
                     if (a.out.bf16) *reinterpret_cast<uint2*>(Ob + d) = make_uint2(0u, 0u);
                     else *reinterpret_cast<float4*>(Of + d) = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
-                if (hl == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = -INFINITY;
+                if (lsub == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = -INFINITY;
             }
             if (++c_item >= item1) return;
             next_index(cit);
@@ -426,54 +462,37 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             pending -= QOPS;
             wait_for(pending);
             lane_of(cit);
+            if constexpr (TR == 16) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + qaddr[s]));
+                for (int s = 0; s < KS16; ++s) qf16[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + qaddr16[s]));
 #pragma unroll
-            for (int i = 0; i < DB; ++i)
+                for (int i = 0; i < DB16; ++i) Oacc16[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+            } else {
 #pragma unroll
-                for (int k = 0; k < 16; ++k) Oacc[i][k] = 0.f;
+                for (int s = 0; s < KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(sb + qaddr[s]));
+#pragma unroll
+                for (int i = 0; i < DB; ++i)
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) Oacc[i][k] = 0.f;
+            }
             m_used = -INFINITY;
             mc = 0.f;
             lsum = 0.f;
             // the fragments must be in registers before a later copy may overwrite this slot
+            if constexpr (TR == 16) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[s]));
+                for (int s = 0; s < KS16; ++s) asm volatile("" : "+v"(qf16[s]));
+            } else {
+#pragma unroll
+                for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[s]));
+            }
             asm volatile("" ::: "memory");
         } else {
             pending -= KVOPS;
             wait_for(pending);
             unsigned char* const vstage = smem + (sb - smem) + VSLOT;   // the V part of this element
-            // S^T = K Q^T
-            floatx16 S;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                uintx4 kv;
-                if constexpr (FP8) {
-                    const unsigned __attribute__((ext_vector_type(2))) kc =
-                        *reinterpret_cast<const unsigned __attribute__((ext_vector_type(2)))*>(sb + kaddr[s]);
-                    kv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, false));
-                    kv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, true));
-                    kv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, false));
-                    kv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, true));
-                } else {
-                    kv = *reinterpret_cast<const uintx4*>(sb + kaddr[s]);
-                }
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S, 0, 0, 0);
-            }
-            // keys outside [key0, min(ke, vis_end)): stage rows before the stage's first key (window clamp), rows past
-            // the range, and rows that this lane's query does not see yet
             const int key0 = cit.ks + c_el * KT;
             const int k0c = min(key0, cit.kwin);
-            if (k0c != key0 || key0 + KT > cit.ke || key0 + KT > causal_from) {
-                const int lo_i = key0 - k0c - 4 * hl, hi_i = min(cit.ke, vis_end) - k0c - 4 * hl;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int ri = 8 * (i >> 2) + (i & 3);   // stage row of element i is ri + 4*hl
-                    if (ri < lo_i || ri >= hi_i) S[i] = -INFINITY;
-                }
-            }
             if (PAGED && key0 + KT > cit.ke) {
                 // the rows past the range are a page's unwritten tail (or another page altogether): clear their V rows
                 // in LDS, since their zero probabilities would still turn a NaN into a NaN in the second product
@@ -509,68 +528,172 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                     }
                 }
             }
-            float tmax = fmaxf(S[0], S[1]);
+            if constexpr (TR == 16) {
+                // S^T = K Q^T, two tiles of 16 keys: element i of tile kg is the score of stage row 16 kg + 4 lg + i
+                floatx4 S4[2];
 #pragma unroll
-            for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, S[i]), S[i + 1]);
-            tmax = half_max(tmax);
-            if (__any(tmax > m_used + tau_raw)) {
-                const float m_new = fmaxf(m_used, tmax);
-                // equal maxima (also -inf and -inf: a row that has seen no key yet) keep the accumulators
-                const float alpha = (m_new == m_used) ? 1.0f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
-                m_used = m_new;
-                mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
-                lsum *= alpha;
+                for (int kg = 0; kg < 2; ++kg) S4[kg] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < DB; ++i)
+                for (int s = 0; s < KS16; ++s) {
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) Oacc[i][k] *= alpha;
-            }
-            // P^T = 2^(S*c2 - m*c2), packed to bf16 in B-operand order (elements 8*tt .. 8*tt+7 are the k-slots of key half tt)
-            uintx4 pb[2];
+                    for (int kg = 0; kg < 2; ++kg) {
+                        const uintx4 kv = *reinterpret_cast<const uintx4*>(sb + kaddr16[kg][s]);
+                        S4[kg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv), qf16[s], S4[kg], 0, 0, 0);
+                    }
+                }
+                if (k0c != key0 || key0 + KT > cit.ke || key0 + KT > causal_from) {
+                    const int lo_i = key0 - k0c - 4 * lg, hi_i = min(cit.ke, vis_end) - k0c - 4 * lg;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
+                    for (int kg = 0; kg < 2; ++kg)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int ri = 16 * kg + i;
+                            if (ri < lo_i || ri >= hi_i) S4[kg][i] = -INFINITY;
+                        }
+                }
+                float tmax = fmaxf(fmaxf(fmaxf(S4[0][0], S4[0][1]), fmaxf(S4[0][2], S4[0][3])),
+                                   fmaxf(fmaxf(S4[1][0], S4[1][1]), fmaxf(S4[1][2], S4[1][3])));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16));      // the four lanes that share a row
+                tmax = half_max(tmax);
+                if (__any(tmax > m_used + tau_raw)) {
+                    const float m_new = fmaxf(m_used, tmax);
+                    const float alpha = (m_new == m_used) ? 1.0f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
+                    m_used = m_new;
+                    mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+                    lsum *= alpha;
+#pragma unroll
+                    for (int i = 0; i < DB16; ++i)
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) Oacc16[i][k] *= alpha;
+                }
+                // P^T as B operand: k-slot e of this lane is element e % 4 of tile e / 4
                 float p[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    p[i] = __builtin_amdgcn_exp2f(fmaf(S[8 * tt + i], c2, -mc));
+                    p[i] = __builtin_amdgcn_exp2f(fmaf(S4[i >> 2][i & 3], c2, -mc));
                     lsum += p[i];
                 }
-                pb[tt] = uintx4{pack_pair(p[0], p[1]), pack_pair(p[2], p[3]), pack_pair(p[4], p[5]), pack_pair(p[6], p[7])};
-            }
-            // O^T += V^T P^T
+                const uintx4 pb = uintx4{pack_pair(p[0], p[1]), pack_pair(p[2], p[3]), pack_pair(p[4], p[5]), pack_pair(p[6], p[7])};
+                // O^T += V^T P^T, 16 columns per MFMA
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
+                for (int db = 0; db < DB16; ++db) {
+                    const unsigned char* vp = vstage + vaddr16[db];
+                    const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                    const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 16 * ROWB));
+                    const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    Oacc16[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb), Oacc16[db], 0, 0, 0);
+                }
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
+                for (int db = 0; db < DB16; ++db) asm volatile("" : "+v"(Oacc16[db]));
+                asm volatile("" ::: "memory");
+            } else {
+                // S^T = K Q^T
+                floatx16 S;
+    #pragma unroll
+                for (int i = 0; i < 16; ++i) S[i] = 0.f;
+    #pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    uintx4 kv;
                     if constexpr (FP8) {
-                        typedef int intx2 __attribute__((ext_vector_type(2)));
-                        const unsigned char* vp = vstage + vaddr8[db] + tt * 2048;     // keys 16 tt ..: two copy blocks further
-                        const intx2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) intx2*)HG_LDS(vp));
-                        uintx4 vv;
-                        vv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, false));
-                        vv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, true));
-                        vv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, false));
-                        vv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, true));
-                        Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                        const unsigned __attribute__((ext_vector_type(2))) kc =
+                            *reinterpret_cast<const unsigned __attribute__((ext_vector_type(2)))*>(sb + kaddr[s]);
+                        kv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, false));
+                        kv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, true));
+                        kv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, false));
+                        kv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, true));
                     } else {
-                        const unsigned char* vp = vstage + vaddr[db] + tt * 16 * ROWB;
-                        const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
-                        const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
-                        const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                        kv = *reinterpret_cast<const uintx4*>(sb + kaddr[s]);
+                    }
+                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[s], S, 0, 0, 0);
+                }
+                // keys outside [key0, min(ke, vis_end)): stage rows before the stage's first key (window clamp), rows past
+                // the range, and rows that this lane's query does not see yet
+                if (k0c != key0 || key0 + KT > cit.ke || key0 + KT > causal_from) {
+                    const int lo_i = key0 - k0c - 4 * hl, hi_i = min(cit.ke, vis_end) - k0c - 4 * hl;
+    #pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int ri = 8 * (i >> 2) + (i & 3);   // stage row of element i is ri + 4*hl
+                        if (ri < lo_i || ri >= hi_i) S[i] = -INFINITY;
                     }
                 }
+                float tmax = fmaxf(S[0], S[1]);
+    #pragma unroll
+                for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, S[i]), S[i + 1]);
+                tmax = half_max(tmax);
+                if (__any(tmax > m_used + tau_raw)) {
+                    const float m_new = fmaxf(m_used, tmax);
+                    // equal maxima (also -inf and -inf: a row that has seen no key yet) keep the accumulators
+                    const float alpha = (m_new == m_used) ? 1.0f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
+                    m_used = m_new;
+                    mc = (m_new == -INFINITY) ? 0.f : m_new * c2;
+                    lsum *= alpha;
+    #pragma unroll
+                    for (int i = 0; i < DB; ++i)
+    #pragma unroll
+                        for (int k = 0; k < 16; ++k) Oacc[i][k] *= alpha;
+                }
+                // P^T = 2^(S*c2 - m*c2), packed to bf16 in B-operand order (elements 8*tt .. 8*tt+7 are the k-slots of key half tt)
+                uintx4 pb[2];
+    #pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    float p[8];
+    #pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        p[i] = __builtin_amdgcn_exp2f(fmaf(S[8 * tt + i], c2, -mc));
+                        lsum += p[i];
+                    }
+                    pb[tt] = uintx4{pack_pair(p[0], p[1]), pack_pair(p[2], p[3]), pack_pair(p[4], p[5]), pack_pair(p[6], p[7])};
+                }
+                // O^T += V^T P^T
+    #pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+    #pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        if constexpr (FP8) {
+                            typedef int intx2 __attribute__((ext_vector_type(2)));
+                            const unsigned char* vp = vstage + vaddr8[db] + tt * 2048;     // keys 16 tt ..: two copy blocks further
+                            const intx2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) intx2*)HG_LDS(vp));
+                            uintx4 vv;
+                            vv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, false));
+                            vv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, true));
+                            vv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, false));
+                            vv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, true));
+                            Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                        } else {
+                            const unsigned char* vp = vstage + vaddr[db] + tt * 16 * ROWB;
+                            const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                            const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 8 * ROWB));
+                            const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                            Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb[tt]), Oacc[db], 0, 0, 0);
+                        }
+                    }
+                }
+                // the accumulators depend on every fragment read of this step: once they are pinned here the reads have
+                // completed, and the next produce_one() may overwrite the slot
+    #pragma unroll
+                for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(Oacc[db]));
+                asm volatile("" ::: "memory");
             }
-            // the accumulators depend on every fragment read of this step: once they are pinned here the reads have
-            // completed, and the next produce_one() may overwrite the slot
-#pragma unroll
-            for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(Oacc[db]));
-            asm volatile("" ::: "memory");
         }
         if (++c_el == cit.nst) {
             // last stage of the item: write (O, LSE) of the part
-            const float ltot = half_sum(lsum);
-            if (rv) {
+            float lsub = lsum;
+            if constexpr (TR == 16) lsub += __shfl_xor(lsub, 16);
+            const float ltot = half_sum(lsub);
+            if (rv && TR == 16) {
+                float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
+                const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+#pragma unroll
+                for (int db = 0; db < DB16; ++db) {     // element i of block db is column 16 db + 4 lg + i of this lane's row
+                    const int d = 16 * db + 4 * lg;
+                    const float o0 = Oacc16[db][0] * inv, o1 = Oacc16[db][1] * inv, o2 = Oacc16[db][2] * inv, o3 = Oacc16[db][3] * inv;
+                    if (a.out.bf16) *reinterpret_cast<uint2*>(Ob + d) = make_uint2(pack_bf16(o0, o1), pack_bf16(o2, o3));
+                    else *reinterpret_cast<float4*>(Of + d) = make_float4(o0, o1, o2, o3);
+                }
+                if (lg == 0) a.out.LSE[(int64_t)cit.c * a.out.part_stride_L + qidx] = ltot > 0.f ? m_used * kscale + __logf(ltot) : -INFINITY;
+            }
+            if (rv && TR == 32) {
                 float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
                 uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
                 const float inv = ltot > 0.f ? (FP8 ? a.v_scale / ltot : 1.0f / ltot) : 0.f;    // a row that sees no key of this chunk: O = 0, LSE = -inf
@@ -608,6 +731,10 @@ static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
         } else {
             return hipErrorInvalidValue;   // 8-bit rows on the matrix cores: D = 128 only
         }
+    } else if (a.tile_rows == 16) {
+        if (a.pg.table) decode_mfma_kernel<D, NS, true, false, false, 16><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        else if (a.seg) decode_mfma_kernel<D, NS, false, true, false, 16><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
+        else decode_mfma_kernel<D, NS, false, false, false, 16><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else if (a.pg.table) {
         decode_mfma_kernel<D, NS, true, false><<<(unsigned)grid, 64, 2 * NS * STB, s>>>(a);
     } else if (a.seg) {
@@ -618,11 +745,12 @@ static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Work items: B * nchunks * ceil(nq*G / 32) * Hkv, adjacent ids on adjacent KV heads of the same rows; a.ipw
+// Work items: B * nchunks * ceil(nq*G / tile_rows) * Hkv, adjacent ids on adjacent KV heads of the same rows; a.ipw
 // consecutive items per wavefront (= workgroup).
 hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s) {
     if (a.items == 0) return hipSuccess;
     if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
+    if (a.tile_rows != 32 && (a.tile_rows != 16 || a.fp8)) return hipErrorInvalidValue;
     if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
     if (D == 128) return launch_decode_mfma_t<128>(a, s);
     if (D == 64) return launch_decode_mfma_t<64>(a, s);

@@ -91,7 +91,7 @@ def test_suffix_attn(idx, chunk):
     ctx.close()
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3, 4], ids=["valu", "mfma", "mfma_ipw3", "mfma_ipw1000"])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5], ids=["valu", "mfma", "mfma_ipw3", "mfma_ipw1000", "mfma_tile32"])
 @pytest.mark.parametrize("chunk", [0, 32, 96])
 @pytest.mark.parametrize("case", ["mha", "gqa8", "gqa4_nq3", "mha_nq5", "gqa8_nq7_two_row_tiles", "long", "d64_gqa8", "d64_mha_nq3", "d64_long"])
 def test_suffix_kernels(case, chunk, kernel):
@@ -125,8 +125,10 @@ def test_suffix_kernels(case, chunk, kernel):
     dw = dev.to_device(w)
     ctx = dev.make_context(dw, parts=24)
     ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, min(kernel, 2))
-    if kernel > 2:   # several work items per wavefront: copies of the next item are in flight while one finishes
+    if kernel in (3, 4):   # several work items per wavefront: copies of the next item are in flight while one finishes
         ctx.set_option(hb.HG_OPT_SUFFIX_ITEMS_PER_WAVE, 3 if kernel == 3 else 1000)
+    if kernel == 5:        # 32-row tiles also where 16-row tiles would be chosen (at most 16 rows per KV head)
+        ctx.set_option(hb.HG_OPT_SUFFIX_TILE_ROWS, 32)
     if chunk:
         ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
     Oref, Lref = oracle.attention(w)
