@@ -359,6 +359,11 @@ def test_error_paths_launch_nothing():
     assert lib.hg_suffix_attn(ctx.h, p(dw.Q), p(dw.Ks), p(dw.Vs), p(dw.offsets), p(dw.lengths), -5, 4, 4, 4, 64, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_INVALID_ARG
     # a suffix so long that 32-bit byte offsets inside one sequence's rows would overflow
     assert lib.hg_suffix_attn(ctx.h, p(dw.Q), p(dw.Ks), p(dw.Vs), p(dw.offsets), p(dw.lengths), 1 << 23, 4, 4, 4, 64, 0.0, p(O), hb.HG_F32, p(L)) == hb.HG_ERR_UNSUPPORTED
+    # options out of range
+    for opt, bad in ((hb.HG_OPT_SUFFIX_TILE_ROWS, 7), (hb.HG_OPT_SUFFIX_KERNEL, 3), (hb.HG_OPT_SUFFIX_ITEMS_PER_WAVE, 5000)):
+        with pytest.raises(hb.HydragenError) as e:
+            ctx.set_option(opt, bad)
+        assert e.value.code == hb.HG_ERR_INVALID_ARG
     # fused call needs room for levels+1 partials: one part is not enough
     with pytest.raises(hb.HydragenError) as e:
         dev.hydragen(ctx, dw, torch.float32)
