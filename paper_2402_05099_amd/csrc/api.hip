@@ -249,7 +249,7 @@ int run_decode(const void* Q, int n_levels, const LevelDev* lv, const void* Ks, 
     if (mfma) {
         a.seg = seg ? 1 : 0;
         // up to 16 rows per KV head and sequence fit a 16-row tile: half the matrix and softmax work per stage
-        a.tile_rows = (nq * a.G <= 16 && !fmt.fp8 && mfma_tile != 32) ? 16 : 32;
+        a.tile_rows = (nq * a.G <= 16 && mfma_tile != 32) ? 16 : 32;
         const int64_t items = (int64_t)B * nchunks * ceil_div(nq * a.G, a.tile_rows) * Hkv;
         if (items >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
         a.items = (int)items;

@@ -78,11 +78,11 @@ __device__ __forceinline__ void wait_vm() {
 // SEG: the key range of sequence b is the block of level a.lv[0] that covers b (the non-decomposed comparison walks
 // the shared blocks per sequence); every query of the sequence sees all of it.
 // TR: query rows per tile.  32: v_mfma_f32_32x32x16_bf16, a lane owns row l % 32 and half of a stage's keys.  16 (when a
-// KV head serves at most 16 rows of a sequence, bf16 rows): v_mfma_f32_16x16x32_bf16, a lane owns row l % 16 and a
-// quarter of the keys; half the matrix work, half the softmax arithmetic and half the registers per stage.
+// KV head serves at most 16 rows of a sequence): v_mfma_f32_16x16x32_bf16, a lane owns row l % 16 and a quarter of
+// the keys; half the matrix work, half the softmax arithmetic and half the registers per stage.
 template <int D, int NS, bool PAGED, bool SEG, bool FP8 = false, int TR = 32>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_mfma_kernel(DecodeArgs a) {
-    static_assert(TR == 32 || (TR == 16 && !FP8), "16-row tiles: bf16 rows only");
+    static_assert(TR == 32 || TR == 16, "query rows per tile");
     using G_ = Geo<D>;
     constexpr int KS = G_::KS, DB = G_::DB, CPR = G_::CPR, RPI = G_::RPI, CPS = G_::CPS, ROWB = G_::ROWB, STB = G_::STB;
     static_assert(NS >= 2 && (NS - 1) * 2 * CPS <= 63, "the copies in flight must fit the vmcnt counter");
@@ -234,6 +234,24 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 #pragma unroll
         for (int db = 0; db < DB16; ++db)
             vaddr16[db] = (unsigned)(vrow * ROWB + (((2 * db + (q4 >> 1)) ^ G_::vswz(vrow)) * 16) + (q4 & 1) * 8);
+        if constexpr (FP8) {
+            // codes, rows in copy order: K row ln of key group kg, columns 32 s + 8 lg .. +7 (8 bytes); V^T through
+            // ds_read_b64_tr_b8 as for 32-row tiles, lane s of a group pointing at the key of k-slot s / 2
+            // (16 (j / 4) + 4 lg + j % 4) and columns 16 db + 8 (s % 2) .. +7; V chunks swizzled by (r/2) % 2 + 2 ((r/16) % 2)
+#pragma unroll
+            for (int s = 0; s < KS16; ++s)
+#pragma unroll
+                for (int kg = 0; kg < 2; ++kg) {
+                    const int row = 16 * kg + ln;
+                    kaddr16[kg][s] = (unsigned)((row >> 3) * 1024 + (row & 7) * 128 + (((2 * s + (lg >> 1)) ^ ((row >> 1) & 7)) * 16) + 8 * (lg & 1));
+                }
+            const int j = ln >> 1, pp = ln & 1;
+            const int row = 16 * (j >> 2) + 4 * lg + (j & 3);
+            const int fsw = ((row >> 1) & 1) | (((row >> 4) & 1) << 1);
+#pragma unroll
+            for (int db = 0; db < DB16; ++db)
+                vaddr16[db] = (unsigned)((row >> 3) * 1024 + (row & 7) * 128 + ((db ^ fsw) * 16) + 8 * pp);
+        }
     }
     // FP8, V^T: ds_read_b64_tr_b8 works on groups of 16 lanes: every lane supplies the address of 8 bytes, and lane i
     // of the group receives, as byte j, byte i % 8 of the piece that lane 2 j + i / 8 of the group pointed at.  So
@@ -291,7 +309,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 if (FP8) {
                     // codes land in copy order (lane l of copy i holds row 8i + l/8), chunks swizzled for the fragment reads
                     voffK[i] = ro + (unsigned)((schg ^ ((srow >> 1) & 7)) * 16);
-                    voffV[i] = ro + (unsigned)((schg ^ (((srow >> 1) & 1) | (((srow >> 3) & 1) << 1))) * 16);
+                    voffV[i] = ro + (unsigned)((schg ^ (((srow >> 1) & 1) | (((srow >> (TR == 16 ? 4 : 3)) & 1) << 1))) * 16);
                 } else {
                     voffK[i] = ro + (unsigned)((sch ^ G_::kswz(srow)) * 16);
                     voffV[i] = ro + (unsigned)((sch ^ G_::vswz(srow)) * 16);
@@ -537,7 +555,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
                 for (int s = 0; s < KS16; ++s) {
 #pragma unroll
                     for (int kg = 0; kg < 2; ++kg) {
-                        const uintx4 kv = *reinterpret_cast<const uintx4*>(sb + kaddr16[kg][s]);
+                        uintx4 kv;
+                        if constexpr (FP8) {
+                            const unsigned __attribute__((ext_vector_type(2))) kc =
+                                *reinterpret_cast<const unsigned __attribute__((ext_vector_type(2)))*>(sb + kaddr16[kg][s]);
+                            kv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, false));
+                            kv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[0], 1.0f, true));
+                            kv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, false));
+                            kv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(kc[1], 1.0f, true));
+                        } else {
+                            kv = *reinterpret_cast<const uintx4*>(sb + kaddr16[kg][s]);
+                        }
                         S4[kg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv), qf16[s], S4[kg], 0, 0, 0);
                     }
                 }
@@ -578,10 +606,21 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 #pragma unroll
                 for (int db = 0; db < DB16; ++db) {
                     const unsigned char* vp = vstage + vaddr16[db];
-                    const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
-                    const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 16 * ROWB));
-                    const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    Oacc16[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb), Oacc16[db], 0, 0, 0);
+                    if constexpr (FP8) {
+                        typedef int intx2 __attribute__((ext_vector_type(2)));
+                        const intx2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) intx2*)HG_LDS(vp));
+                        uintx4 vv;
+                        vv[0] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, false));
+                        vv[1] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[0], 1.0f, true));
+                        vv[2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, false));
+                        vv[3] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)vc[1], 1.0f, true));
+                        Oacc16[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb), Oacc16[db], 0, 0, 0);
+                    } else {
+                        const shortx4 vlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp));
+                        const shortx4 vhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)HG_LDS(vp + 16 * ROWB));
+                        const shortx8 vv = __builtin_shufflevector(vlo, vhi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        Oacc16[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), __builtin_bit_cast(bf16x8, pb), Oacc16[db], 0, 0, 0);
+                    }
                 }
 #pragma unroll
                 for (int db = 0; db < DB16; ++db) asm volatile("" : "+v"(Oacc16[db]));
@@ -683,7 +722,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
             if (rv && TR == 16) {
                 float* const Of = static_cast<float*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
                 uint16_t* const Ob = static_cast<uint16_t*>(a.out.O) + (int64_t)cit.c * a.out.part_stride_O + qidx * D;
-                const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+                const float inv = ltot > 0.f ? (FP8 ? a.v_scale / ltot : 1.0f / ltot) : 0.f;
 #pragma unroll
                 for (int db = 0; db < DB16; ++db) {     // element i of block db is column 16 db + 4 lg + i of this lane's row
                     const int d = 16 * db + 4 * lg;
@@ -726,8 +765,14 @@ static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
         if constexpr (D == 128) {
             if (a.seg) return hipErrorInvalidValue;
             // (rings of 3 and 4 slots, two and three elements in flight: 77 and 78 us against 76 on config 4)
-            if (a.pg.table) decode_mfma_kernel<D, NS, true, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
-            else decode_mfma_kernel<D, NS, false, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+            if (a.tile_rows == 16) {
+                if (a.pg.table) decode_mfma_kernel<D, NS, true, false, true, 16><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+                else decode_mfma_kernel<D, NS, false, false, true, 16><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+            } else if (a.pg.table) {
+                decode_mfma_kernel<D, NS, true, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+            } else {
+                decode_mfma_kernel<D, NS, false, false, true><<<(unsigned)grid, 64, NS * STB, s>>>(a);
+            }
         } else {
             return hipErrorInvalidValue;   // 8-bit rows on the matrix cores: D = 128 only
         }
@@ -750,7 +795,7 @@ static hipError_t launch_decode_mfma_t(const DecodeArgs& a, hipStream_t s) {
 hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s) {
     if (a.items == 0) return hipSuccess;
     if (a.ipw < 1 || a.n_levels != (a.seg ? 1 : 0) || (a.seg && a.pg.table)) return hipErrorInvalidValue;
-    if (a.tile_rows != 32 && (a.tile_rows != 16 || a.fp8)) return hipErrorInvalidValue;
+    if (a.tile_rows != 32 && a.tile_rows != 16) return hipErrorInvalidValue;
     if (a.pg.table && (a.pg.shift < 4 || a.pg.stride < 1 || a.pg.n_pages < 1)) return hipErrorInvalidValue;
     if (D == 128) return launch_decode_mfma_t<128>(a, s);
     if (D == 64) return launch_decode_mfma_t<64>(a, s);

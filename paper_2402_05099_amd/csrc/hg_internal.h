@@ -82,7 +82,7 @@ struct DecodeArgs {
     int chunk;        // keys per work item
     int nchunks;      // work items per (sequence, KV head, query-head group)
     int64_t units;    // B * nq * nchunks * Hkv * (G / GT)
-    int tile_rows;    // matrix-core kernel: query rows per tile, 32 or 16 (16: at most 16 rows per KV head and sequence, bf16 rows)
+    int tile_rows;    // matrix-core kernel: query rows per tile, 32 or 16 (16: at most 16 rows per KV head and sequence)
     int items;        // matrix-core kernel: B * nchunks * ceil(nq*G / tile_rows) * Hkv work items
     int ipw;          // matrix-core kernel: consecutive work items per wavefront
     int seg;          // matrix-core kernel: 1 = the keys of sequence b are the rows of the block of lv[0] that covers b

@@ -35,7 +35,14 @@ def finite_codes(n_rows: int) -> np.ndarray:
     return np.broadcast_to(row.reshape(1, 2, 128), (n_rows, 2, 128)).copy()
 
 
-KERNELS = pytest.mark.parametrize("kernel", [1, 2], ids=["valu", "mfma"])
+KERNELS = pytest.mark.parametrize("kernel", [1, 2, 3], ids=["valu", "mfma", "mfma_tile32"])
+
+
+def choose_kernel(ctx, kernel):
+    """1: vector-ALU; 2: matrix cores (16-row tiles where a KV head serves at most 16 rows); 3: matrix cores, 32-row tiles."""
+    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, min(kernel, 2))
+    if kernel == 3:
+        ctx.set_option(hb.HG_OPT_SUFFIX_TILE_ROWS, 32)
 
 
 @KERNELS
@@ -48,7 +55,7 @@ def test_every_value_code_is_decoded_exactly(kernel):
     Q = dev.bf16_tensor(wl.normal_bf16(1, 0, (B, H, D)), "cuda:0")
     offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
     ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
-    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
+    choose_kernel(ctx, kernel)
     O = torch.full((B, H, D), float("nan"), dtype=torch.float32, device="cuda:0")
     L = torch.full((B, H), float("nan"), dtype=torch.float32, device="cuda:0")
     v_scale = 0.37
@@ -77,7 +84,7 @@ def test_every_key_code_is_decoded_exactly(kernel):
     Q = dev.bf16_tensor(wl.f32_to_bf16_bits(q), "cuda:0")
     offsets, lengths = i32(np.arange(B)), i32(np.ones(B))
     ctx = hb.Context(0, hb.hg_workspace_bytes(B, H, D, 4))
-    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
+    choose_kernel(ctx, kernel)
     O = torch.empty((B, H, D), dtype=torch.float32, device="cuda:0")
     L = torch.empty((B, H), dtype=torch.float32, device="cuda:0")
     k_scale, scale = 0.75, 0.25
@@ -87,7 +94,7 @@ def test_every_key_code_is_decoded_exactly(kernel):
     want = 2.0 * vals.T * k_scale * scale                           # [B = d, H]
     got = L.cpu().numpy().astype(np.float64)
     assert np.allclose(got, want, rtol=2e-6, atol=1e-9), float(np.abs(got - want).max())
-    assert np.allclose(O.cpu().numpy(), np.ones((B, H, D), dtype=np.float32), rtol=1e-5 if kernel == 2 else 0.0, atol=0.0)
+    assert np.allclose(O.cpu().numpy(), np.ones((B, H, D), dtype=np.float32), rtol=1e-5 if kernel >= 2 else 0.0, atol=0.0)
     ctx.close()
 
 
@@ -113,7 +120,7 @@ def test_suffix_attn_fp8(case, chunk, out_dtype, kernel):
     dw = dev.to_device(w)
     f8 = wl.make_fp8(w, reserve=5)                  # unowned rows hold a NaN code
     ctx = dev.make_context(dw, parts=24)
-    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)  # 2: the matrix-core kernel wherever D = 128 (D = 64 stays on the vector ALU)
+    choose_kernel(ctx, kernel)   # an 8-bit cache at D = 64 stays on the vector ALU
     if chunk:
         ctx.set_option(hb.HG_OPT_SUFFIX_CHUNK, chunk)
     Oref, Lref = fp8.suffix_attention_fp8(w.Q, w.Hkv, f8.Ks8, f8.Vs8, f8.k_scale, f8.v_scale, f8.offsets, w.lengths, w.scale)
@@ -324,7 +331,7 @@ def test_paged_fp8_suffix_and_fused(case, page_size, kernel):
     K8, V8, offs = oracle.paged_to_packed(pg.K, pg.V, pg.table, pg.page_size, w.lengths)
     Os, Ls = fp8.suffix_attention_fp8(w.Q, w.Hkv, K8, V8, ks, vs, offs, w.lengths, w.scale)
     ctx = dev.make_context(dw, parts=24)
-    ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, kernel)
+    choose_kernel(ctx, kernel)
     O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.float32, device="cuda:0")
     L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
     hb.hg_suffix_attn_paged(ctx, dw.Q, kv, dw.lengths, dw.max_len, O, L, dw.scale)
