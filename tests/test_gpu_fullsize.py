@@ -1,6 +1,7 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (default options, bf16 output,
-24 workspace parts): the five configurations and the paper's microbenchmark shape, with the oracle evaluated on sampled sequences (first, last,
-shortest and longest suffix, block boundaries of the tree) and whole-output properties checked at full size."""
+24 workspace parts): the five configurations and the paper's microbenchmark shape.  Every row of O and LSE, of the
+fused call and of the non-decomposed comparison call, is compared with the oracle (the oracle takes about 13 s for
+the largest configuration on the GPU machine's host cores)."""
 import sys
 
 import numpy as np
@@ -16,43 +17,38 @@ from parity import check, to_np
 pytestmark = pytest.mark.gpu
 
 
+_capsys = None
+
+
+@pytest.fixture(autouse=True)
+def _uncaptured(capsys):
+    """The figures of every comparison are printed past pytest's capture, so that they show in a quiet run too."""
+    global _capsys
+    _capsys = capsys
+    yield
+    _capsys = None
+
+
 def say(msg):
-    print(msg, file=sys.stderr, flush=True)
+    if _capsys is not None:
+        with _capsys.disabled():
+            print(msg, file=sys.stderr, flush=True)
+    else:
+        print(msg, file=sys.stderr, flush=True)
 
 
-def sample_seqs(w, extra=()):
-    s = {0, w.B - 1, w.B // 2, int(np.argmin(w.lengths)), int(np.argmax(w.lengths))}
-    for lv in w.levels:
-        if lv.Gn > 1:
-            s.update([int(lv.seq_off[1]) - 1, int(lv.seq_off[1]), int(lv.seq_off[lv.Gn - 1])])
-    s.update(extra)
-    return np.array(sorted(s), dtype=np.int32)
-
-
-def run_and_check(w, dw, what, with_naive=True):
+def run_and_check(w, dw, what):
     ctx = dev.make_context(dw, parts=24)
-    seqs = sample_seqs(w)
-    Oref, Lref = oracle.attention(w, seqs=seqs)
-    idx = torch.from_numpy(seqs.astype(np.int64)).cuda()
+    Oref, Lref = oracle.attention(w)                       # every sequence, every head
     O, L = dev.hydragen(ctx, dw, torch.bfloat16)
     torch.cuda.synchronize()
-    st = check(to_np(O[idx]), to_np(L[idx]), Oref, Lref, what, out_bf16=True)
-    say(f"   {what}: {st}")
-    # properties that hold for every row at any size
-    assert bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(L).all())
-    # the full LSE is at least each part's LSE: compare with the suffix-only part on all rows
-    Os = torch.empty((dw.B, dw.Hq, dw.D), dtype=torch.float32, device="cuda:0")
-    Ls = torch.empty((dw.B, dw.Hq), dtype=torch.float32, device="cuda:0")
-    hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, Os, Ls, dw.scale)
+    st = check(to_np(O), to_np(L), Oref, Lref, what, out_bf16=True)
+    say(f"   {what}: all {w.B * w.Hq} rows: max|dO|={st['max_abs_dO']:.3e} (max|O|={st['max_abs_O']:.3e}) rel-L2={st['rel_l2']:.3e} "
+        f"max|dLSE|={st['max_abs_dLSE']:.3e}")
+    On, Ln = dev.naive(ctx, dw, torch.bfloat16)
     torch.cuda.synchronize()
-    assert bool((L >= Ls - 1e-4).all())
-    if with_naive:
-        On, Ln = dev.naive(ctx, dw, torch.bfloat16)
-        torch.cuda.synchronize()
-        check(to_np(On[idx]), to_np(Ln[idx]), Oref, Lref, what + " naive", out_bf16=True)
-        # decomposed and non-decomposed results agree on every row
-        assert float((On.float() - O.float()).abs().max()) <= 2.0 ** -6 * float(O.float().abs().max())
-        assert float((Ln - L).abs().max()) <= 1e-3
+    sn = check(to_np(On), to_np(Ln), Oref, Lref, what + " naive", out_bf16=True)
+    say(f"   {what} non-decomposed call: max|dO|={sn['max_abs_dO']:.3e} rel-L2={sn['rel_l2']:.3e} max|dLSE|={sn['max_abs_dLSE']:.3e}")
     ctx.close()
 
 
@@ -72,7 +68,7 @@ def test_full_config3_prefix_sweep():
         w.levels[0] = wl.Level(K=full.K[:P], V=full.V[:P], kv_off=np.array([0, P], np.int32), seq_off=full.seq_off)
         assert np.array_equal(w.levels[0].K, wl.config(3, P=1024).levels[0].K) if P == 1024 else True
         dw = dev.to_device(w)
-        run_and_check(w, dw, f"config3 P={P}", with_naive=(P != 16384))
+        run_and_check(w, dw, f"config3 P={P}")
         del dw
         torch.cuda.empty_cache()
 
