@@ -61,10 +61,11 @@ extern "C" {
 
 typedef struct hg_ctx hg_ctx;
 
-enum { HG_OK = 0, HG_ERR_INVALID_ARG = 1, HG_ERR_UNSUPPORTED = 2, HG_ERR_WORKSPACE = 3, HG_ERR_HIP = 4 };
+enum { HG_OK = 0, HG_ERR_INVALID_ARG = 1, HG_ERR_UNSUPPORTED = 2, HG_ERR_WORKSPACE = 3, HG_ERR_HIP = 4, HG_ERR_STATIC_LIMIT = 5 };
 enum { HG_F32 = 0, HG_BF16 = 1 };
 enum { HG_KV_BF16 = 0, HG_KV_E4M3 = 1 }; /* element format of a paged suffix cache (hg_paged_kv.kv_format) */
 enum { HG_MAX_LEVELS = 4, HG_MAX_PARTS = 64 };
+enum { HG_STATIC_SCRATCH_BYTES = 67108864 }; /* 64 MiB: partial-result memory of hg_hydragen_attn_static */
 
 /* Tunables for hg_set_option (0 = library default). */
 enum {
@@ -165,6 +166,27 @@ int hg_hydragen_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* l
                      const void* Ks, const void* Vs, const int32_t* offsets, const int32_t* lengths, int max_len,
                      int B, int Hq, int Hkv, int D, float scale,
                      void* O_out, int o_dtype, float* LSE_out);
+
+/*
+ * hg_hydragen_attn for callers that cannot hand the library memory from an allocator and must not trigger an
+ * allocation themselves: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result and same kernels as hg_hydragen_attn, but the fp32 partial results live in a fixed array of
+ * HG_STATIC_SCRATCH_BYTES (64 MiB) inside the library's device image instead of the context's workspace (which may
+ * be absent: hg_create(.., NULL, 0)); the call allocates and frees nothing, on the device or through any library.
+ * Every GPU the library is loaded on holds the array until the process ends; its address is looked up by hg_create
+ * on the context's device.
+ * Limit: one partial result per non-empty shared level plus one for the suffix must fit, i.e.
+ *   (levels + 1) * B * nq * Hq * (D + 1) * 4 <= HG_STATIC_SCRATCH_BYTES   (two parts at D = 128: B * nq * Hq <= 65027),
+ * else HG_ERR_STATIC_LIMIT and nothing is enqueued; with room to spare, long key ranges are split as in
+ * hg_hydragen_attn.  Devices numbered 64 and above: HG_ERR_UNSUPPORTED.
+ * All calls on one GPU share the array, whatever their context or stream: two such calls that overlap in time on one
+ * GPU race on it (calls ordered on one stream do not).  Nothing in it needs to start at zero and nothing is kept
+ * from call to call: every part a merge reads is written, or marked empty, by that call's own kernels.
+ */
+int hg_hydragen_attn_static(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* levels,
+                            const void* Ks, const void* Vs, const int32_t* offsets, const int32_t* lengths, int max_len,
+                            int B, int Hq, int Hkv, int D, float scale,
+                            void* O_out, int o_dtype, float* LSE_out);
 
 /*
  * Paged suffix cache.  Sec. 3.5 contrasts Hydragen's plain suffix cache with PagedAttention's paged one (see also

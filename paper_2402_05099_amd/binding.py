@@ -13,7 +13,8 @@ from typing import List, Optional, Sequence
 
 import torch
 
-HG_OK, HG_ERR_INVALID_ARG, HG_ERR_UNSUPPORTED, HG_ERR_WORKSPACE, HG_ERR_HIP = 0, 1, 2, 3, 4
+HG_OK, HG_ERR_INVALID_ARG, HG_ERR_UNSUPPORTED, HG_ERR_WORKSPACE, HG_ERR_HIP, HG_ERR_STATIC_LIMIT = 0, 1, 2, 3, 4, 5
+HG_STATIC_SCRATCH_BYTES = 64 << 20
 HG_F32, HG_BF16 = 0, 1
 HG_MAX_LEVELS, HG_MAX_PARTS = 4, 64
 HG_OPT_PREFIX_SPLITS, HG_OPT_SUFFIX_CHUNK, HG_OPT_OVERLAP, HG_OPT_NAIVE_CHUNK, HG_OPT_STAGE_TIMING, HG_OPT_PREFIX_KERNEL = 1, 2, 3, 4, 5, 6
@@ -34,6 +35,7 @@ EXPORTS = (
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
     "hg_debug_wide_plan", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
+    "hg_hydragen_attn_static",
 )
 
 
@@ -93,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.hg_hydragen_attn.restype = ci
         L.hg_naive_attn.argtypes = fused
         L.hg_naive_attn.restype = ci
+        L.hg_hydragen_attn_static.argtypes = fused
+        L.hg_hydragen_attn_static.restype = ci
         L.hg_suffix_attn_paged.argtypes = [vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci, ci, cf, vp, ci, vp]
         L.hg_suffix_attn_paged.restype = ci
         L.hg_hydragen_attn_paged.argtypes = [vp, vp, ci, ctypes.POINTER(hg_level), ctypes.POINTER(hg_paged_kv), vp, ci,
@@ -323,6 +327,12 @@ def _fused(fn, name, ctx, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_
 def hg_hydragen_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,
                      scale: float = 0.0) -> None:
     _fused(lib().hg_hydragen_attn, "hg_hydragen_attn", ctx, Q, levels, Ks, Vs, offsets, lengths, max_len, O_out, LSE_out, scale)
+
+
+def hg_hydragen_attn_static(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,
+                            scale: float = 0.0) -> None:
+    _fused(lib().hg_hydragen_attn_static, "hg_hydragen_attn_static", ctx, Q, levels, Ks, Vs, offsets, lengths, max_len, O_out,
+           LSE_out, scale)
 
 
 def hg_naive_attn(ctx: Context, Q, levels: List[Level], Ks, Vs, offsets, lengths, max_len: int, O_out, LSE_out=None,

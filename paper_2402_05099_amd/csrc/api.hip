@@ -2,6 +2,7 @@
 // no host synchronisation, no copies: every entry point only enqueues kernels on the context's stream.
 #include <math.h>
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "hg_internal.h"
@@ -30,6 +31,14 @@ struct hg_ctx {
     long long tcalls;      // fused calls recorded since timing was enabled
 };
 
+// Partial-result memory of hg_hydragen_attn_static, the fused call for callers that cannot provide a workspace from an
+// allocator: a fixed array in the library's device image (every GPU the library is loaded on holds its own copy until
+// the process ends).  In host code the array's name is only a handle for hipGetSymbolAddress: the address a kernel may
+// use is looked up once per device in hg_create and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[HG_STATIC_SCRATCH_BYTES];
+static unsigned char* g_scratch_ptr[64];   // per device, set by hg_create on that device
+static std::mutex g_scratch_mu;
+
 namespace {
 
 using namespace hg;
@@ -47,15 +56,17 @@ struct Parts {   // fp32 partial results carved out of the workspace
     float* l(int p) const { return L + (int64_t)p * rows; }
 };
 
-Parts carve(const hg_ctx* c, int64_t rows, int D) {
+struct Ws { unsigned char* p; size_t bytes; };   // device memory that holds the partial results of one call
+
+Parts carve(const Ws& ws, int64_t rows, int D) {
     Parts p{};
     p.rows = rows;
     p.D = D;
     const size_t per = (size_t)rows * (D + 1) * sizeof(float);
-    size_t cap = (c->ws && per) ? c->ws_bytes / per : 0;
+    size_t cap = (ws.p && per) ? ws.bytes / per : 0;
     if (cap > HG_MAX_PARTS) cap = HG_MAX_PARTS;
     p.cap = (int)cap;
-    p.O = reinterpret_cast<float*>(c->ws);
+    p.O = reinterpret_cast<float*>(ws.p);
     p.L = p.O + (int64_t)p.cap * rows * D;
     return p;
 }
@@ -341,6 +352,15 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return HG_ERR_HIP;
     if (hipSetDevice(device) != hipSuccess) return HG_ERR_HIP;
+    if (device < 64) {
+        // this device's copy of the static scratch array (hg_hydragen_attn_static); the device is current here
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        if (!g_scratch_ptr[device]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HG_ERR_HIP;
+            g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+        }
+    }
     hg_ctx* c = new (std::nothrow) hg_ctx();
     if (!c) return HG_ERR_HIP;
     c->device = device;
@@ -459,7 +479,7 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     const int nq = c->opt_nq;
     const int64_t rows = (int64_t)B * nq * Hq;
     const LevelDev lv = to_dev(*level, B);
-    const Parts parts = carve(c, rows, D);
+    const Parts parts = carve(Ws{c->ws, c->ws_bytes}, rows, D);
     const LevelPlan plan = plan_level(c, lv, Hkv, nq * (Hq / Hkv), D, parts.cap);
     const int ns = plan.ns;
     hipStream_t s = c->stream;
@@ -506,7 +526,7 @@ static int suffix_impl(hg_ctx* c, const void* Q, const void* Ks, const void* Vs,
     const int64_t rows = (int64_t)B * nq * Hq;
     hipStream_t s = c->stream;
     if (max_len == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
-    const Parts parts = carve(c, rows, D);
+    const Parts parts = carve(Ws{c->ws, c->ws_bytes}, rows, D);
     const int max_chunk = pg.table ? 32 << pg.shift : 1 << 30;
     SuffixPlan p = plan_suffix(c, max_len, Hq / Hkv, B, nq, Hkv, D, pg.table != nullptr, max_chunk, fmt.fp8 != 0);
     if (p.nchunks > parts.cap) {  // not enough room for partials: fewer, longer chunks
@@ -619,7 +639,8 @@ static int check_fused(hg_ctx* c, const void* Q, int n_levels, const hg_level* l
 // hg_hydragen_attn and hg_hydragen_attn_paged (pg.table set, offsets unused)
 static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
                       const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
-                      float scale, void* O_out, int o_dtype, float* LSE_out, const hg::PagedDev& pg, const KvFmt& fmt = KvFmt{}) {
+                      float scale, void* O_out, int o_dtype, float* LSE_out, const hg::PagedDev& pg, const KvFmt& fmt = KvFmt{},
+                      const Ws* ws_override = nullptr) {
     int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype,
                          pg.table != nullptr);
     if (rc) return rc;
@@ -630,7 +651,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     const int64_t rows = (int64_t)B * nq * Hq;
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
-    const Parts parts = carve(c, rows, D);
+    const Parts parts = carve(ws_override ? *ws_override : Ws{c->ws, c->ws_bytes}, rows, D);
 
     // plan: parts per level and for the suffix, shrunk to fit the workspace
     LevelDev lv[HG_MAX_LEVELS];
@@ -776,6 +797,24 @@ int hg_hydragen_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* lev
                       LSE_out, hg::PagedDev{});
 }
 
+int hg_hydragen_attn_static(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const void* Ks, const void* Vs,
+                            const int32_t* offsets, const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D,
+                            float scale, void* O_out, int o_dtype, float* LSE_out) {
+    if (!c) return HG_ERR_INVALID_ARG;
+    if (c->device < 0 || c->device >= 64 || !g_scratch_ptr[c->device]) return HG_ERR_UNSUPPORTED;
+    int rc = check_fused(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, O_out, o_dtype);
+    if (rc) return rc;
+    // one fp32 partial result per non-empty shared level and one for the suffix must fit the array
+    int need = (Ks != nullptr && max_len > 0) ? 1 : 0;
+    for (int i = 0; i < n_levels; ++i)
+        if (levels[i].max_rows > 0 && (levels[i].kv_off ? levels[i].max_seqs : B) > 0) ++need;
+    const unsigned long long per = (unsigned long long)B * c->opt_nq * Hq * (D + 1) * sizeof(float);
+    if ((unsigned long long)need * per > (unsigned long long)HG_STATIC_SCRATCH_BYTES) return HG_ERR_STATIC_LIMIT;
+    const Ws ws{g_scratch_ptr[c->device], (size_t)HG_STATIC_SCRATCH_BYTES};
+    return fused_impl(c, Q, n_levels, levels, Ks, Vs, offsets, lengths, max_len, B, Hq, Hkv, D, scale, O_out, o_dtype,
+                      LSE_out, hg::PagedDev{}, KvFmt{}, &ws);
+}
+
 int hg_hydragen_attn_paged(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels, const hg_paged_kv* kv,
                            const int32_t* lengths, int max_len, int B, int Hq, int Hkv, int D, float scale, void* O_out,
                            int o_dtype, float* LSE_out) {
@@ -870,7 +909,7 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
     const int64_t rows = (int64_t)B * nq * Hq;
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
-    const Parts parts = carve(c, rows, D);
+    const Parts parts = carve(Ws{c->ws, c->ws_bytes}, rows, D);
     LevelDev lv[HG_MAX_LEVELS];
     int64_t nmax = has_suffix ? max_len : 0;
     for (int i = 0; i < n_levels; ++i) {
@@ -976,6 +1015,7 @@ const char* hg_strerror(int code) {
         case HG_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case HG_ERR_WORKSPACE: return "workspace too small";
         case HG_ERR_HIP: return "HIP runtime error";
+        case HG_ERR_STATIC_LIMIT: return "too many query rows for the static scratch array of hg_hydragen_attn_static";
     }
     return "unknown error";
 }

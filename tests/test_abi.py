@@ -43,7 +43,7 @@ def test_workspace_bytes_and_strerror(lib):
 
 def test_constants_match_header():
     text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
-    for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_F32", "HG_BF16",
+    for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_ERR_STATIC_LIMIT", "HG_STATIC_SCRATCH_BYTES", "HG_F32", "HG_BF16",
                  "HG_MAX_LEVELS", "HG_MAX_PARTS", "HG_OPT_PREFIX_SPLITS", "HG_OPT_SUFFIX_CHUNK", "HG_OPT_OVERLAP",
                  "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_OPT_PREFIX_KERNEL", "HG_TIMING_RING", "HG_OPT_WIDE_SLOTS",
                  "HG_OPT_NUM_QUERIES", "HG_OPT_SUFFIX_KERNEL", "HG_OPT_SUFFIX_ITEMS_PER_WAVE", "HG_OPT_SUFFIX_TILE_ROWS", "HG_KV_BF16", "HG_KV_E4M3"):
@@ -75,6 +75,7 @@ def test_calls_without_a_context_are_rejected_before_any_device_work(lib):
     assert lib.hg_hydragen_attn(z, z, 0, ctypes.byref(lv), z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
     assert lib.hg_hydragen_attn_fp8(z, z, 0, ctypes.byref(lv), z, z, 1.0, 1.0, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
     assert lib.hg_naive_attn(z, z, 0, ctypes.byref(lv), z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
+    assert lib.hg_hydragen_attn_static(z, z, 0, ctypes.byref(lv), z, z, z, z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
     assert lib.hg_suffix_attn_paged(z, z, ctypes.byref(kv), z, 1, 1, 1, 1, 128, 0.0, z, 0, z) == bad
     assert lib.hg_kv_append(z, z, z, z, z, z, z, 1, 1, 1, 128) == bad
     assert lib.hg_kv_append_fp8(z, z, z, z, z, 1.0, 1.0, z, z, 1, 1, 1, 128) == bad
