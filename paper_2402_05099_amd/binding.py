@@ -450,10 +450,10 @@ def hg_kv_append_paged(ctx: Context, Knew, Vnew, kv: PagedKV, lengths, capacity:
 
 def hg_debug_wide_plan(n_blocks: int, max_rows: int, max_seqs: int, Hkv: int, rows_per_seq: int, max_parts: int, slots_per_xcd: int):
     """dict of the persistent shared-block kernel's work partition, or None if the level does not fit (host only)."""
-    out = (ctypes.c_int * 8)()
+    out = (ctypes.c_int * 9)()
     if not lib().hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, out):
         return None
-    return dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts"), list(out)))
+    return dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts", "mode"), list(out)))
 
 
 def hg_debug_suffix_plan(B: int, nq: int, Hq: int, Hkv: int, D: int, max_len: int, page_size: int = 0):

@@ -29,9 +29,11 @@ def hipcc() -> str:
 PER_SOURCE_FLAGS = {}   # source file name -> extra hipcc flags
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    """Compile every source to an object (sources may carry their own flags), then link the shared library."""
-    objdir = os.path.join(PKG, "_build")
+def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
+    """Compile every source to an object (sources may carry their own flags), then link the shared library.
+    `out` other than the default names a variant build (e.g. one compiled with -DHG_TRACE, see prefix_wide.hip):
+    select it at run time with HYDRAGEN_LIB=<path>."""
+    objdir = os.path.join(PKG, "_build" if out == LIB else "_build_" + os.path.basename(out))
     os.makedirs(objdir, exist_ok=True)
     cc = hipcc()
     common = [f for f in HIPCC_FLAGS if f != "-shared"]
@@ -48,13 +50,13 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     for cmd, pr in procs:
         if pr.wait() != 0:
             raise subprocess.CalledProcessError(pr.returncode, cmd)
-    tmp = LIB + f".tmp{os.getpid()}"
+    tmp = out + f".tmp{os.getpid()}"
     link = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.check_call(link)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 def is_stale() -> bool:
@@ -66,4 +68,11 @@ def is_stale() -> bool:
 
 
 if __name__ == "__main__":
-    build(extra_flags=sys.argv[1:])
+    # usage: python -m paper_2402_05099_amd.build [--out variant.so] [extra hipcc flags...]
+    argv = sys.argv[1:]
+    target = LIB
+    if "--out" in argv:
+        i = argv.index("--out")
+        target = os.path.abspath(argv[i + 1])
+        del argv[i:i + 2]
+    build(extra_flags=argv, out=target)

@@ -986,7 +986,7 @@ int hg_read_stage_timings(hg_ctx* c, float* ms, int n_calls) {
 }
 
 int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts, int slots_per_xcd,
-                       int out[8]) {
+                       int out[9]) {
     if (!out || n_blocks < 1 || max_rows < 0 || max_seqs < 0 || Hkv < 1 || rows_per_seq < 1) return 0;
     hg::LevelDev lv{};
     lv.n_blocks = n_blocks;
@@ -995,7 +995,7 @@ int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int ro
     hg::WidePlan p{};
     if (!hg::plan_prefix_wide(lv, Hkv, rows_per_seq, max_parts, slots_per_xcd, &p)) return 0;
     out[0] = p.n_c; out[1] = p.ncols; out[2] = p.rowgroups; out[3] = p.T;
-    out[4] = p.slots; out[5] = p.tpx; out[6] = p.quota; out[7] = p.nparts;
+    out[4] = p.slots; out[5] = p.tpx; out[6] = p.quota; out[7] = p.nparts; out[8] = p.mode;
     return 1;
 }
 

@@ -4,7 +4,8 @@
 
 A step is 16 MFMAs in a fixed order (8 for the scores of the next 32 keys, 8 for P*V of the current 32 keys).
 Between them go, in fixed places: the step's vector-ALU work (exponentials of the current scores, packing to bf16,
-fp32 row sums, row maxima of the next scores), its two HBM->LDS copy instructions and its 24 LDS fragment reads.  Every
+fp32 row sums, row maxima of the next scores), its two HBM->LDS copy instructions (addressed by the kernel's copy
+cursor `cur`, which runs NS-1 stages ahead of the piece `pc` being computed) and its 24 LDS fragment reads.  Every
 gap ends in a scheduling barrier so that the compiler keeps this order: a wavefront then always has a matrix
 instruction in flight while it issues vector-ALU instructions, instead of running the two kinds back to back.
 
@@ -39,12 +40,12 @@ def build():
             else:        # keys 0..15 of stage j+1, for the next step
                 post = [f"vf[{db}] = lds_v(slot1, 0, {db});"]
             mf.append((f"mfma_acc(Oacc[{db}], vf[{db}], pb[{tt}]);", [], post))
-    # the copy of stage j+NS-1: scalar address arithmetic in gap 0, the two copy instructions in gaps 1 and 3
-    mf[0][1].extend(["const int cp_k0 = min(ks + (j + NS - 1) * KT, kwin);",
-                     "const int64_t cp_off = (int64_t)cp_k0 * rstride_b;",
+    # the copy that keeps the ring NS-1 stages ahead (the copy cursor may already be in a later piece): scalar address
+    # arithmetic in gap 0, the two copy instructions in gaps 1 and 3
+    mf[0][1].extend(["const int64_t cp_off = (int64_t)min(cur.ks + cur.t * KT, cur.kwin) * rstride_b;",
                      "const unsigned cp_dst = ldsw + (unsigned)((slot + NS - 1) & (NS - 1)) * STB;"])
-    mf[1][1].append("copy16(Kg + cp_off, voffK, cp_dst);")
-    mf[3][1].append("copy16(Vg + cp_off, voffV, cp_dst + VRING);")
+    mf[1][1].append("copy16(cur.Kg + cp_off, cur.voffK, cp_dst);")
+    mf[3][1].append("copy16(cur.Vg + cp_off, cur.voffV, cp_dst + VRING);")
 
     crit, late = [], []     # (cycles, statement, earliest gap, deadline gap)
     n = 0
@@ -91,7 +92,7 @@ def build():
                 s = crit[ci]; ci += 1
             elif g >= MAX_FROM and mi < len(mx):
                 if first_max:
-                    out.append("if (check_mask && j + 1 >= nfull && j + 1 < nst) mask_stage(Snext, j + 1);")
+                    out.append("if (kMasked) mask_stage(Snext, j + 1);")
                     first_max = False
                 s = mx[mi]; mi += 1
             elif li < len(late):

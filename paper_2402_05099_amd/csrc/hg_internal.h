@@ -39,8 +39,11 @@ struct WidePlan {
     int T;          // workgroups per team = query-row tiles per row group
     int slots;      // workgroups (CUs) per XCD that the kernel occupies
     int tpx;        // teams per XCD (slots / T)
-    int quota;      // stages per team
+    int quota;      // stages per team (mode 0)
     int nparts;     // partial results per query row
+    int mode;       // how the flattened (column, stage) space is cut into one contiguous range per team:
+                    // 0: equal ranges of `quota` stages; 1: ranges that never straddle a column boundary (each column
+                    // cut evenly among its own teams, or whole columns per team when there are more columns than teams)
 };
 
 struct PrefixArgs {
@@ -132,8 +135,8 @@ hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, 
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
 
-constexpr int kPrefixRowsNarrow = 128;  // query rows per workgroup, 32-rows-per-wavefront kernel
-constexpr int kPrefixRowsWide = 256;    // query rows per workgroup, 64-rows-per-wavefront kernel
+constexpr int kPrefixRowsNarrow = 128;  // query rows per workgroup of the 128-row kernel (4 wavefronts x 32 rows)
+constexpr int kPrefixRowsWide = 256;    // query rows per workgroup of the persistent kernel (8 wavefronts x 32 rows)
 constexpr int kPrefixKeys = 64;         // keys per prefix LDS tile
 
 // ---- small device helpers -------------------------------------------------------------------------

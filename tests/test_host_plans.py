@@ -1,7 +1,8 @@
 """Host logic of the library, checked without a GPU: the work partition of the persistent shared-block kernel must
 cover every (column, stage) position exactly once within the partial results it promises, for any level shape, CU
-count and workspace; the suffix planner must respect its limits.  The walk below is the kernel's own rule (team t owns
-flattened positions [t*quota, (t+1)*quota); part index = team - floor(column * n_c / quota)), restated in Python."""
+count and workspace; the suffix planner must respect its limits.  The walk below is the kernel's own rule (mode 0:
+team t owns flattened positions [t*quota, (t+1)*quota), part index = team - floor(column * n_c / quota); mode 1: ranges
+aligned to the columns), restated in Python."""
 import itertools
 
 import numpy as np
@@ -15,16 +16,29 @@ def walk(plan):
     n_c, ncols, quota = plan["n_c"], plan["ncols"], plan["quota"]
     total = ncols * n_c
     pieces = {}
-    for team in range(8 * plan["tpx"]):
-        f0, f1 = team * quota, min((team + 1) * quota, total)
+    nteams = 8 * plan["tpx"]
+    for team in range(nteams):
+        if plan["mode"] == 0:
+            f0, f1 = team * quota, (team + 1) * quota
+            sp = team - (f0 // n_c * n_c) // quota
+        elif ncols <= nteams:
+            c = team * ncols // nteams
+            tf = -(-c * nteams // ncols)
+            nt = -(-(c + 1) * nteams // ncols) - tf
+            sp = team - tf
+            f0, f1 = c * n_c + sp * n_c // nt, c * n_c + (sp + 1) * n_c // nt
+        else:
+            f0, f1 = team * ncols // nteams * n_c, (team + 1) * ncols // nteams * n_c
+            sp = 0
+        f0, f1 = min(f0, total), min(f1, total)
         c, k0 = divmod(f0, n_c) if f0 < f1 else (0, 0)
         while f0 < f1:
             ln = min(n_c - k0, f1 - f0)
-            sp = team - (c * n_c) // quota
             pieces.setdefault(c, []).append((k0, ln, sp, team))
             f0 += ln
             c += 1
             k0 = 0
+            sp = 0          # a later piece of the same team starts its column
     return pieces
 
 
@@ -60,7 +74,25 @@ def test_wide_plan_covers_every_stage_once(shape, slots, max_parts):
         assert [p[2] for p in ps] == list(range(len(ps))), "part indices count the pieces of the column from 0"
         assert len(ps) <= plan["nparts"]
     # the teams that exist can take the whole space
-    assert 8 * plan["tpx"] * plan["quota"] >= plan["ncols"] * plan["n_c"]
+    if plan["mode"] == 0:
+        assert 8 * plan["tpx"] * plan["quota"] >= plan["ncols"] * plan["n_c"]
+
+
+def test_wide_plan_aligns_short_pieces_to_columns():
+    """Config 2's shape (40 columns of 64 stages on 256 teams): ranges of 10 stages would cut 32 teams' ranges at a
+    column boundary (two pieces, each with its fixed price); aligned ranges give every team one piece of 9..11 stages."""
+    plan = hb.hg_debug_wide_plan(1, 2048, 256, 40, 1, 24, 32)
+    assert plan["mode"] == 1 and plan["nparts"] == 7
+    pieces = walk(plan)
+    per_team = {}
+    for c, ps in pieces.items():
+        for (k0, ln, sp, team) in ps:
+            per_team.setdefault(team, []).append(ln)
+    assert all(len(v) == 1 for v in per_team.values()) and len(per_team) == 256
+    assert max(v[0] for v in per_team.values()) == 11 and min(v[0] for v in per_team.values()) == 9
+    # long columns keep equal ranges (config 3 at 16K keys: 64 teams x 320 stages)
+    plan = hb.hg_debug_wide_plan(1, 16384, 1024, 40, 1, 24, 32)
+    assert plan["mode"] == 0 and plan["quota"] == 320
 
 
 def test_wide_plan_rejects_what_it_cannot_run():
