@@ -79,6 +79,7 @@ enum {
     HG_OPT_NUM_QUERIES = 8,   /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
     HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10, /* matrix-core suffix kernel: consecutive work items one wavefront takes (1..1024; 0 = automatic) */
     HG_OPT_SUFFIX_TILE_ROWS = 11, /* matrix-core suffix kernel: query rows per tile: 0 automatic (16 when a KV head serves at most 16 rows of a sequence, else 32), 16 (honoured under the same condition), 32 */
+    HG_OPT_FUSED_KERNEL = 12, /* hg_hydragen_attn on a packed bf16 suffix cache: 0 automatic (one launch for the whole call when it holds so little work that launches and partial results would dominate, else one kernel per part and a merge), 1 always the separate kernels, 2 the single launch whenever it applies */
     HG_OPT_SUFFIX_KERNEL = 9  /* suffix kernel: 0 automatic (matrix-core kernel when a KV head serves several query rows of a sequence: two or more queries, three or more query heads, or two heads with max_len >= 256; or when D = 128 and max_len >= 384 whatever the rows; else the vector-ALU kernel), 1 always vector-ALU, 2 always matrix-core; an 8-bit cache with D = 64 is always read by the vector-ALU kernel */
 };
 enum { HG_TIMING_RING = 128, HG_MAX_STAGES = HG_MAX_LEVELS + 2 };

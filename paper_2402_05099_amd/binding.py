@@ -24,6 +24,7 @@ HG_KV_BF16, HG_KV_E4M3 = 0, 1
 HG_OPT_SUFFIX_KERNEL = 9
 HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10
 HG_OPT_SUFFIX_TILE_ROWS = 11
+HG_OPT_FUSED_KERNEL = 12
 HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)
@@ -198,6 +199,9 @@ class PagedKV:
 class Context:
     """Owns an hg_ctx and its workspace tensor (device memory comes from PyTorch)."""
 
+    # {option: value} set on every new context right after hg_create (empty: the library's defaults)
+    default_options: dict = {}
+
     def __init__(self, device: int = 0, workspace_bytes: int = 0, stream: Optional[torch.cuda.Stream] = None):
         L = lib()
         self.device = device
@@ -209,6 +213,8 @@ class Context:
         sp = ctypes.c_void_p(self._stream_handle(stream))
         _check(L.hg_create(ctypes.byref(h), device, sp, _p(self.workspace), workspace_bytes), "hg_create")
         self.h = h
+        for option, value in self.default_options.items():
+            self.set_option(option, value)
 
     def _stream_handle(self, stream) -> int:
         if stream is None:

@@ -22,6 +22,7 @@ struct hg_ctx {
     int opt_suffix_kernel; // 0 automatic, 1 vector-ALU kernel, 2 matrix-core kernel wherever it applies
     int opt_suffix_ipw;    // matrix-core suffix kernel: work items per wavefront (0 automatic)
     int opt_suffix_tile;   // matrix-core suffix kernel: query rows per tile (0 automatic, 16, 32)
+    int opt_fused_kernel;  // fused call: 0 automatic, 1 separate kernels, 2 single launch whenever it applies
     hipStream_t aux;       // second stream for the overlap option
     hipEvent_t ev_fork, ev_join;
     // stage timing ring: slot = call % HG_TIMING_RING, 2 events (begin, end) per stage
@@ -117,7 +118,9 @@ int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
 struct LevelPlan { bool wide; int ns; WidePlan wp; };
 
 // The persistent 256-row kernel (D = 128) runs a level whose blocks have more than 128 query rows; the 128-row
-// kernel runs the rest (small blocks would leave most of a 256-row tile empty) and every D = 64 level.
+// kernel runs the rest and every D = 64 level.  (16 blocks of 128 rows x 512 keys x 40 heads alone: 55 us on the
+// persistent kernel against 63 us; but inside the fused call its workgroups take whole CUs from the suffix kernel, where
+// 128-row workgroups share them: 0.646 against 0.591 ms on the two-level tree.)
 // HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel wherever D = 128.  max_parts bounds the
 // partial results the plan may use.
 // G: query rows per sequence and KV head (queries per sequence x query heads per KV head).
@@ -372,6 +375,7 @@ int hg_create(hg_ctx** out, int device, void* hip_stream, void* workspace, size_
     c->opt_suffix_kernel = 0;
     c->opt_suffix_ipw = 0;
     c->opt_suffix_tile = 0;
+    c->opt_fused_kernel = 0;
     c->aux = nullptr;
     c->ev_fork = c->ev_join = nullptr;
     c->opt_timing = 0;
@@ -437,6 +441,10 @@ int hg_set_option(hg_ctx* c, int option, int value) {
         case HG_OPT_SUFFIX_TILE_ROWS:
             if (value != 0 && value != 16 && value != 32) return HG_ERR_INVALID_ARG;
             c->opt_suffix_tile = value;
+            return HG_OK;
+        case HG_OPT_FUSED_KERNEL:
+            if (value > 2) return HG_ERR_INVALID_ARG;
+            c->opt_fused_kernel = value;
             return HG_OK;
         case HG_OPT_WIDE_SLOTS:
             if (value > 32) return HG_ERR_INVALID_ARG;
@@ -651,6 +659,47 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     const int64_t rows = (int64_t)B * nq * Hq;
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
+
+    // One launch for everything when the call is small (packed bf16 suffix rows only): a workgroup of four wavefronts
+    // per 32-row tile walks every shared block and the tile's suffixes and merges in LDS (fused_small.hip).  A
+    // wavefront's chain of stages bounds the time: about a quarter of (shared keys + suffix keys of the tile's
+    // sequences) / 32 stages of roughly a microsecond, against three launches, two event edges and a round trip of the
+    // partial results through HBM for the separate kernels (about 45 us when there is nothing else to wait for).
+    if (!pg.table && !fmt.fp8 && c->opt_fused_kernel != 1 && !c->opt_timing) {
+        const int rps = nq * G;
+        long long shared_keys = 0;
+        bool any = has_suffix;
+        for (int i = 0; i < n_levels; ++i) {
+            const long long seqs = levels[i].kv_off ? levels[i].max_seqs : B;
+            if (levels[i].max_rows > 0 && seqs > 0) { shared_keys += levels[i].max_rows; any = true; }
+        }
+        const int seqs_per_tile = rps >= 32 ? 1 : (32 + rps - 1) / rps + (32 % rps ? 1 : 0);
+        const long long stages = (shared_keys + 31) / 32 + (has_suffix ? (long long)seqs_per_tile * ((max_len + 31) / 32) : 0);
+        const long long tiles = ((long long)B * rps + 31) / 32;
+        const double waves_rounds = (double)(tiles * Hkv) / 256.0;     // workgroups per CU
+        const double est_us = 6.0 + (double)((stages + 3) / 4) * 1.2 * (waves_rounds > 1.0 ? waves_rounds : 1.0);
+        const bool small = est_us <= 40.0;
+        if (any && tiles * Hkv < (1LL << 31) && (c->opt_fused_kernel == 2 || small)) {
+            SmallArgs sa{};
+            sa.Q = static_cast<const uint16_t*>(Q);
+            sa.n_levels = 0;
+            for (int i = 0; i < n_levels; ++i) {
+                const LevelDev d = to_dev(levels[i], B);
+                if (d.max_rows == 0 || d.max_seqs == 0) continue;
+                sa.lv[sa.n_levels++] = d;
+            }
+            sa.Ks = static_cast<const uint16_t*>(Ks);
+            sa.Vs = static_cast<const uint16_t*>(Vs);
+            sa.offsets = offsets;
+            sa.lengths = has_suffix ? lengths : nullptr;
+            sa.max_len = max_len;
+            sa.B = B; sa.Hq = Hq; sa.Hkv = Hkv; sa.G = G; sa.nq = nq;
+            sa.tiles = (int)tiles;
+            sa.scale = scale;
+            sa.O = O_out; sa.LSE = LSE_out; sa.bf16 = (o_dtype == HG_BF16);
+            return hip_rc(launch_fused_small(sa, D, c->stream));
+        }
+    }
     const Parts parts = carve(ws_override ? *ws_override : Ws{c->ws, c->ws_bytes}, rows, D);
 
     // plan: parts per level and for the suffix, shrunk to fit the workspace

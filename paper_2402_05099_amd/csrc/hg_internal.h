@@ -96,6 +96,25 @@ struct DecodeArgs {
     OutDev out;       // part index = chunk
 };
 
+// The single-launch fused kernel (fused_small.hip): every level, the suffix and the merge for 32-row tiles of query rows.
+struct SmallArgs {
+    const uint16_t* Q;
+    int n_levels;
+    LevelDev lv[HG_MAX_LEVELS];
+    const uint16_t* Ks;
+    const uint16_t* Vs;
+    const int32_t* offsets;
+    const int32_t* lengths;   // null: no suffix
+    int max_len;
+    int B, Hq, Hkv, G;
+    int nq;
+    int tiles;                // 32-row tiles of the B * nq * G query rows of one KV head
+    float scale;
+    void* O;                  // final results: [B, nq, Hq, D] bf16 or fp32, LSE [B, nq, Hq] (may be null)
+    float* LSE;
+    int bf16;
+};
+
 struct MergeArgs {
     const void* O[HG_MAX_PARTS];
     const float* L[HG_MAX_PARTS];
@@ -132,6 +151,7 @@ bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slo
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s);   // matrix-core per-sequence kernel (8-bit rows: D = 128 only)
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
+hipError_t launch_fused_small(const SmallArgs& a, int D, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
 

@@ -24,3 +24,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _separate_kernels_by_default():
+    """The test workloads are small, and on small calls the fused entry point runs everything in one launch
+    (HG_OPT_FUSED_KERNEL = 0).  The tests of the separate kernels, their options and their partitions therefore pin
+    new contexts to the separate kernels; tests of the single launch, and the full-size tests, which run the library's
+    defaults, set the option themselves."""
+    from paper_2402_05099_amd import binding as hb
+    old = dict(hb.Context.default_options)
+    hb.Context.default_options = {hb.HG_OPT_FUSED_KERNEL: 1}
+    yield
+    hb.Context.default_options = old

@@ -46,7 +46,7 @@ def test_constants_match_header():
     for name in ("HG_OK", "HG_ERR_INVALID_ARG", "HG_ERR_UNSUPPORTED", "HG_ERR_WORKSPACE", "HG_ERR_HIP", "HG_ERR_STATIC_LIMIT", "HG_STATIC_SCRATCH_BYTES", "HG_F32", "HG_BF16",
                  "HG_MAX_LEVELS", "HG_MAX_PARTS", "HG_OPT_PREFIX_SPLITS", "HG_OPT_SUFFIX_CHUNK", "HG_OPT_OVERLAP",
                  "HG_OPT_NAIVE_CHUNK", "HG_OPT_STAGE_TIMING", "HG_OPT_PREFIX_KERNEL", "HG_TIMING_RING", "HG_OPT_WIDE_SLOTS",
-                 "HG_OPT_NUM_QUERIES", "HG_OPT_SUFFIX_KERNEL", "HG_OPT_SUFFIX_ITEMS_PER_WAVE", "HG_OPT_SUFFIX_TILE_ROWS", "HG_KV_BF16", "HG_KV_E4M3"):
+                 "HG_OPT_NUM_QUERIES", "HG_OPT_SUFFIX_KERNEL", "HG_OPT_SUFFIX_ITEMS_PER_WAVE", "HG_OPT_SUFFIX_TILE_ROWS", "HG_OPT_FUSED_KERNEL", "HG_KV_BF16", "HG_KV_E4M3"):
         m = re.search(rf"\b{name}\s*=\s*(\d+)", text)
         assert m, name
         assert int(m.group(1)) == getattr(hb, name), name

@@ -39,6 +39,7 @@ def say(msg):
 
 def run_and_check(w, dw, what):
     ctx = dev.make_context(dw, parts=24)
+    ctx.set_option(hb.HG_OPT_FUSED_KERNEL, 0)              # the library's own choice, as bench.py runs it
     Oref, Lref = oracle.attention(w)                       # every sequence, every head
     O, L = dev.hydragen(ctx, dw, torch.bfloat16)
     torch.cuda.synchronize()
