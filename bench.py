@@ -6,15 +6,24 @@ over one synthetic batch that is already resident in HBM.  The default workload 
 configuration the headline metric is quoted on: B=1024 decode queries, MHA 40 heads x 128, shared prefix
 P=16384, ragged suffix lengths uniform in [32,128], bf16, N(0,1) values (seed 3).
 
-Prints ONE JSON line: queries/s per layer, per-kernel rooflines (stage durations measured with HIP events on
-the streams the kernels run on, inside the timed region), the speed-up over the non-decomposed per-sequence
-kernel, and the fp64 CPU oracle timed on a bounded sample of the same workload (which doubles as a parity
-spot check of the timed configuration).
+Prints ONE JSON line: queries/s per layer (mean over the timed region, plus median and minimum of per-step events),
+per-kernel rooflines from a second, serialised pass (stage durations measured with HIP events on the streams the
+kernels run on), the same for the other configurations (`configs`), the chip's own ceilings measured in the same
+run (`ceilings`: a register-only matrix-instruction loop on constant and on random operands, a streaming read), the
+speed-up over the non-decomposed per-sequence kernel, and the fp64 CPU oracle timed on a bounded sample of the same
+workload (which doubles as a parity spot check of the timed configuration).
+
+`--power-table` is a separate mode: three-second loops of the kernels with the board's power sensor sampled
+meanwhile, printed as a text table.
 """
 import argparse
+import glob
+import hashlib
 import json
 import os
+import re
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -23,22 +32,282 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+CSRC = os.path.join(ROOT, "paper_2402_05099_amd", "csrc")
+# the source files each kernel's counters depend on (a stored counter reading is only quoted while they are unchanged)
+KERNEL_SOURCES = {
+    "prefix_level": ["prefix_wide.hip", "prefix_wide_step.inc", "prefix.hip", "prefix_common.h", "hg_internal.h"],
+    "suffix": ["decode.hip", "decode_mfma.hip", "hg_internal.h"],
+}
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/fused_c3_P16384_hbm_traffic.txt),
-# each counter scaled by its reading for a 1 GiB device copy (FETCH_SIZE reads 0.50002 of the true KiB on this
-# chip, WRITE_SIZE 1.0), keyed by (kernel, workload); None for pairs not measured.
-MEASURED_TRAFFIC = {
-    ("prefix_level0", "c3_long_P16384"): int((173540.0 / 0.50002 + 51880.4) * 1024),
-    ("suffix", "c3_long_P16384"): int((834136.4 / 0.50002 + 20804.8) * 1024),
-    ("prefix_level0", "c4_gqa"): int((12480.9 / 0.50003 + 35728.4) * 1024),
-    ("suffix", "c4_gqa"): int((276987.8 / 0.50003 + 16513.9) * 1024),
-}
-# Matrix-core busy fraction of the shared-block kernel from a rocprofv3 --pmc run of its own
-# (profiles/fused_c3_P16384_mfma_util.txt): SQ_VALU_MFMA_BUSY_CYCLES / (active cycles x 1024 SIMDs), and the clock
-# the kernel ran at (active cycles / duration); keyed like MEASURED_TRAFFIC.
-MEASURED_MFMA_UTIL = {
-    ("prefix_level0", "c3_long_P16384"): {"mfma_busy_frac_of_cycles": 0.596, "clock_ghz": 1.81},
-}
+
+def sources_sha16(kind: str) -> str:
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES[kind]:
+        h.update(open(os.path.join(CSRC, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_counters(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload` from the tracked rocprofv3 --pmc summaries under profiles/ (lines
+    `# machine: {...}`), or None if there is none or the kernel's sources have changed since it was taken."""
+    kind = "prefix_level" if kernel.startswith("prefix_level") else kernel
+    if kind not in KERNEL_SOURCES:
+        return None
+    sha = sources_sha16(kind)
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path, errors="replace"):
+            m = re.match(r"#\s*machine:\s*(\{.*\})\s*$", line)
+            if not m:
+                continue
+            try:
+                rec = json.loads(m.group(1))
+            except ValueError:
+                continue
+            if rec.get("kernel") == kernel and rec.get("workload") == workload and rec.get("sources_sha16") == sha:
+                rec["file"] = os.path.relpath(path, ROOT)
+                return rec
+    return None
+
+
+def stats(xs):
+    import numpy as np
+    a = np.asarray(xs, dtype=np.float64)
+    return {"mean": float(a.mean()), "median": float(np.median(a)), "min": float(a.min())}
+
+
+def algorithmic_work(w, fp8_kv=False):
+    """bytes / flops the method itself has to move per launch of each kernel (what the rooflines are priced on)"""
+    import numpy as np
+    B, Hq, Hkv, D, nq = w.B, w.Hq, w.Hkv, w.D, w.nq
+    rows = B * nq * Hq
+    T = int(np.minimum(w.lengths, w.max_len).sum())
+    kv_elem = 1 if fp8_kv else 2
+    suffix_bytes = 2 * kv_elem * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
+    level_flops, level_bytes = [], []
+    for lv in w.levels:
+        f = by = 0
+        for g in range(lv.Gn):
+            nk = int(lv.kv_off[g + 1] - lv.kv_off[g])
+            ns = int(lv.seq_off[g + 1] - lv.seq_off[g])
+            f += 4 * ns * nq * Hq * nk * D
+            by += 4 * nk * Hkv * D + ns * nq * Hq * D * 2 + ns * nq * Hq * (D + 1) * 4
+        level_flops.append(f)
+        level_bytes.append(by)
+    return suffix_bytes, level_flops, level_bytes
+
+
+def kernel_table(w, stage_stats, nlev, fp8_kv=False):
+    """per-kernel rooflines from per-stage duration statistics [suffix, levels.., merge] (ms)"""
+    suffix_bytes, level_flops, level_bytes = algorithmic_work(w, fp8_kv)
+    kernels = {}
+    s = stage_stats[0]
+    if s["mean"] > 0:
+        kernels["suffix"] = {"bound": "hbm", "ms": s["mean"], "ms_median": s["median"], "ms_min": s["min"],
+                             "achieved": suffix_bytes / (s["mean"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "algorithmic": suffix_bytes}
+    for i in range(nlev):
+        s = stage_stats[1 + i]
+        if s["mean"] <= 0:
+            continue
+        ms = s["mean"]
+        tf = level_flops[i] / (ms * 1e-3) / 1e12
+        gb = level_bytes[i] / (ms * 1e-3) / 1e9
+        # a level is priced against the roofline that binds it: flops/byte above ~312 -> matrix cores, else HBM
+        mfma_bound = level_flops[i] / max(level_bytes[i], 1) >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+        base = {"ms": ms, "ms_median": s["median"], "ms_min": s["min"]}
+        kernels[f"prefix_level{i}"] = dict(base, **(
+            {"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "algorithmic": level_flops[i], "hbm_GBs": gb}
+            if mfma_bound else
+            {"bound": "hbm", "achieved": gb, "peak": PEAK_HBM_GBS, "unit": "GB/s", "algorithmic": level_bytes[i], "TFLOPs": tf}))
+    s = stage_stats[1 + nlev]
+    kernels["merge"] = {"bound": "hbm", "ms": s["mean"], "ms_median": s["median"], "ms_min": s["min"], "unit": "GB/s", "peak": PEAK_HBM_GBS}
+    for k in kernels.values():
+        if "achieved" in k:
+            k["frac"] = k["achieved"] / k["peak"]
+    return kernels
+
+
+class Runner:
+    """One workload on the device and the ways of timing the fused call on it."""
+
+    def __init__(self, w, args, hb, dev, torch, variant_step=None):
+        self.w, self.args, self.hb, self.torch = w, args, hb, torch
+        self.dw = dev.to_device(w)
+        torch.cuda.synchronize()
+        self.ctx = dev.make_context(self.dw, parts=args.parts)
+        self.O = torch.empty(self.dw.lead + (self.dw.D,), dtype=torch.bfloat16, device="cuda:0")
+        self.L = torch.empty(self.dw.lead, dtype=torch.float32, device="cuda:0")
+        self._step = variant_step
+
+    def step(self):
+        if self._step is not None:
+            return self._step(self)
+        dw = self.dw
+        self.hb.hg_hydragen_attn(self.ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, self.O, self.L, dw.scale)
+
+    def timed_region(self, n):
+        """n calls between two synchronisations, nothing else enqueued: milliseconds per step (the headline)"""
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    def per_step_events(self, n, flush=None):
+        """n calls, each bracketed by its own pair of events on the stream (optionally a cache-flushing write between
+        them, outside the brackets): statistics of the device-side duration of a call"""
+        torch = self.torch
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        torch.cuda.synchronize()
+        for e0, e1 in ev:
+            if flush is not None:
+                flush.add_(1)
+            e0.record()
+            self.step()
+            e1.record()
+        torch.cuda.synchronize()
+        return stats([e0.elapsed_time(e1) for e0, e1 in ev])
+
+    def staged(self, n):
+        """n calls with the library's per-kernel timing events: (ms per step by the host clock, per-stage statistics)"""
+        hb, torch = self.hb, self.torch
+        import numpy as np
+        self.ctx.set_option(hb.HG_OPT_STAGE_TIMING, 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            self.step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        st = np.array(self.ctx.read_stage_timings(min(n, hb.HG_TIMING_RING)), dtype=np.float64)
+        self.ctx.set_option(hb.HG_OPT_STAGE_TIMING, 0)
+        return (t1 - t0) * 1e3 / n, [stats(st[:, i]) for i in range(st.shape[1])]
+
+    def close(self):
+        self.ctx.close()
+
+
+def measure_config(w, args, hb, dev, torch, steps, warmup):
+    """the default and the serialised pass of one plain configuration (an entry of `configs`)"""
+    r = Runner(w, args, hb, dev, torch)
+    for _ in range(warmup):
+        r.step()
+    ms = r.timed_region(steps)
+    ev = r.per_step_events(steps)
+    r.ctx.set_option(hb.HG_OPT_OVERLAP, 1)
+    for _ in range(3):
+        r.step()
+    serial_ms, st = r.staged(steps)
+    nlev = len(r.dw.levels)
+    out = {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+           "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
+           "suffix_len": [int(w.lengths.min()), int(w.lengths.max())],
+           "ms_per_step": ms, "ms_per_step_events": ev, "queries_per_s": w.B * w.nq / (ms * 1e-3),
+           "ms_per_step_serialised": serial_ms, "kernels": kernel_table(w, st, nlev)}
+    r.close()
+    del r
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure_ceilings(hb, torch, ctx):
+    """what this chip sustains: the matrix instruction alone (constant / random operands) and a streaming read"""
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    iters = 4000
+    flops = 256 * 8 * iters * 16 * 32768.0
+    out = {}
+    for name, rnd in (("mfma_constant_operands", False), ("mfma_random_operands", True)):
+        hb.hg_debug_mfma_loop(ctx, rnd, 200, clocks, sink)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            hb.hg_debug_mfma_loop(ctx, rnd, iters, clocks, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            c = clocks.cpu().numpy()
+            rec = {"TFLOPs": flops / (ms * 1e-3) / 1e12, "clock_GHz": float(c[0]) / max(float(c[1]), 1.0) * 0.1, "ms": ms}
+            if best is None or rec["TFLOPs"] > best["TFLOPs"]:
+                best = rec
+        best["frac_of_peak"] = best["TFLOPs"] / PEAK_BF16_TFLOPS
+        out[name] = best
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    hb.hg_debug_stream_read(ctx, buf, sink)
+    torch.cuda.synchronize()
+    best = 0.0
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        hb.hg_debug_stream_read(ctx, buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    out["stream_read"] = {"GBs": best, "frac_of_peak": best / PEAK_HBM_GBS, "bytes": buf.numel()}
+    del buf
+    torch.cuda.empty_cache()
+    return out
+
+
+def power_table(args, hb, dev, wl, torch):
+    """three-second loops of the kernels of config 3 and of the two ceiling kernels, board power sampled every 20 ms"""
+    files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") + glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+    cap = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+    def power():
+        for f in files:
+            try:
+                return int(open(f).read().strip()) / 1e6
+            except (OSError, ValueError):
+                pass
+        return float("nan")
+    w = wl.config(args.config, P=args.prefix or None)
+    r = Runner(w, args, hb, dev, torch)
+    dw, ctx = r.dw, r.ctx
+    lv = dw.levels[0]
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    Of = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+    print(f"# board power while one call is repeated for 3 s ({w.name}); sensor {files[:1]}, cap {[open(c).read().strip() for c in cap[:1]]} uW, idle {power():.0f} W")
+    print("# loop | ms per call | mean W | max W | clock GHz (matrix loops: shader cycles / 100 MHz ticks inside the kernel)")
+    def run(name, fn, clock=False):
+        samples, stop = [], [False]
+        def poll():
+            while not stop[0]:
+                samples.append((time.time(), power()))
+                time.sleep(0.02)
+        th = threading.Thread(target=poll)
+        th.start()
+        t0, n = time.time(), 0
+        while time.time() - t0 < 3.0:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+            n += 20
+        dt = time.time() - t0
+        stop[0] = True
+        th.join()
+        ps = [p for (t, p) in samples if t - t0 > 1.0]
+        ghz = ""
+        if clock:
+            c = clocks.cpu().numpy()
+            ghz = f"{float(c[0]) / max(float(c[1]), 1.0) * 0.1:.2f}"
+        print(f"{name} | {dt / n * 1e3:.4f} | {sum(ps) / max(len(ps), 1):.0f} | {max(ps) if ps else float('nan'):.0f} | {ghz}", flush=True)
+        time.sleep(1.0)
+    run("matrix instruction loop, constant operands (4000 x 16 per wavefront)", lambda: hb.hg_debug_mfma_loop(ctx, False, 4000, clocks, sink), True)
+    run("matrix instruction loop, random operands", lambda: hb.hg_debug_mfma_loop(ctx, True, 4000, clocks, sink), True)
+    run("streaming read, 2 GiB", lambda: hb.hg_debug_stream_read(ctx, buf, sink))
+    run("suffix kernel", lambda: hb.hg_suffix_attn(ctx, dw.Q, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, Of, r.L, dw.scale))
+    run("shared-block kernel (+ its merge)", lambda: hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, Of, r.L, dw.scale))
+    run("fused call, default", r.step)
+    ctx.set_option(hb.HG_OPT_OVERLAP, 1)
+    run("fused call, serialised", r.step)
+    r.close()
+    return 0
 
 
 def main() -> int:
@@ -64,8 +333,13 @@ def main() -> int:
     ap.add_argument("--append-steps", type=int, default=0, help="also time this many KV-cache updates (hg_kv_append / _paged), reported as kv_append_ms")
     ap.add_argument("--nq", type=int, default=1, help="queries per sequence (App. B's num_queries: the last nq suffix tokens are queried at once); a variant, value then counts B * nq queries")
     ap.add_argument("--suffix-kernel", type=int, default=0, help="HG_OPT_SUFFIX_KERNEL: 0 automatic, 1 vector-ALU, 2 matrix-core")
+    ap.add_argument("--fused-kernel", type=int, default=0, help="HG_OPT_FUSED_KERNEL: 0 automatic, 1 separate kernels, 2 single launch whenever it applies")
     ap.add_argument("--graph", action="store_true", help="also time the fused call replayed from a captured HIP graph (reported as graph_ms_per_step; the headline stays the eager call)")
     ap.add_argument("--wide-slots", type=int, default=0, help="HG_OPT_WIDE_SLOTS: CUs per XCD for the persistent shared-block kernel (0 = library default)")
+    ap.add_argument("--flush-mib", type=int, default=0, help="per-step events pass: write a buffer of this many MiB between steps (more than the 256 MiB last-level cache), reported as ms_per_step_events_flushed")
+    ap.add_argument("--extra-configs", type=int, default=-1, help="1: also measure configs 2, 3 at P=1024/4096, 4 and 5 (`configs`); default: only in the plain headline run")
+    ap.add_argument("--ceilings", type=int, default=-1, help="1: also measure the matrix-instruction and streaming-read ceilings (`ceilings`); default: only in the plain headline run")
+    ap.add_argument("--power-table", action="store_true", help="separate mode: board power while each kernel of the workload is repeated for three seconds; prints a text table")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -83,16 +357,36 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     hb.lib()  # fail loudly if the HIP library is missing
+    if args.power_table:
+        return power_table(args, hb, dev, wl, torch)
+
+    plain = (args.config == 3 and not (args.prefix or args.batch or args.suffix_len or args.paged or args.fp8_kv or args.nq > 1
+                                       or args.splits or args.overlap or args.suffix_chunk or args.prefix_kernel
+                                       or args.suffix_kernel or args.fused_kernel or args.wide_slots))
+    want_configs = plain if args.extra_configs < 0 else bool(args.extra_configs)
+    want_ceilings = plain if args.ceilings < 0 else bool(args.ceilings)
 
     t0 = time.time()
     variant = {"nq": args.nq} if args.nq > 1 else {}
     w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None, **variant)
-    dw = dev.to_device(w)
-    torch.cuda.synchronize()
+
+    kv = None
+    f8 = None          # packed 8-bit cache
+    f8_paged = None    # (PagedSuffix of codes, k_scale, v_scale)
+
+    def variant_step(r):
+        dw = r.dw
+        if f8 is not None:
+            hb.hg_hydragen_attn_fp8(r.ctx, dw.Q, dw.levels, dK8, dV8, f8.k_scale, f8.v_scale, doff8, dw.lengths, dw.max_len, r.O, r.L, dw.scale)
+        elif kv is not None:
+            hb.hg_hydragen_attn_paged(r.ctx, dw.Q, dw.levels, kv, dw.lengths, dw.max_len, r.O, r.L, dw.scale)
+        else:
+            hb.hg_hydragen_attn(r.ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, r.O, r.L, dw.scale)
+
+    r = Runner(w, args, hb, dev, torch, variant_step)
+    dw, ctx, O, L = r.dw, r.ctx, r.O, r.L
     print(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} levels={[int(l.K.shape[0]) for l in w.levels]} "
           f"T={w.T} (generated + uploaded in {time.time() - t0:.1f}s)", file=sys.stderr, flush=True)
-
-    ctx = dev.make_context(dw, parts=args.parts)
     if args.splits:
         ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, args.splits)
     if args.suffix_chunk:
@@ -102,13 +396,8 @@ def main() -> int:
     if args.wide_slots:
         ctx.set_option(hb.HG_OPT_WIDE_SLOTS, args.wide_slots)
     ctx.set_option(hb.HG_OPT_SUFFIX_KERNEL, args.suffix_kernel)
+    ctx.set_option(hb.HG_OPT_FUSED_KERNEL, args.fused_kernel)
 
-    O = torch.empty(dw.lead + (dw.D,), dtype=torch.bfloat16, device="cuda:0")
-    L = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
-
-    kv = None
-    f8 = None          # packed 8-bit cache
-    f8_paged = None    # (PagedSuffix of codes, k_scale, v_scale)
     if args.paged and args.fp8_kv:
         f8_paged = wl.make_paged_fp8(w, args.paged, reserve=args.append_steps)
         pg8 = f8_paged[0]
@@ -125,16 +414,8 @@ def main() -> int:
         doff8 = torch.from_numpy(f8.offsets).cuda()
         torch.cuda.synchronize()
 
-    def step():
-        if f8 is not None:
-            hb.hg_hydragen_attn_fp8(ctx, dw.Q, dw.levels, dK8, dV8, f8.k_scale, f8.v_scale, doff8, dw.lengths, dw.max_len, O, L, dw.scale)
-        elif kv is not None:
-            hb.hg_hydragen_attn_paged(ctx, dw.Q, dw.levels, kv, dw.lengths, dw.max_len, O, L, dw.scale)
-        else:
-            hb.hg_hydragen_attn(ctx, dw.Q, dw.levels, dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
-
     for _ in range(args.warmup):
-        step()
+        r.step()
     torch.cuda.synchronize()
     if args.calibration_copy_mib > 0:   # a copy kernel of known size: reads and writes exactly this many bytes
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -144,32 +425,26 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    def timed(n):
-        """n fused calls bracketed by synchronisation; returns (ms per step, mean stage ms [suffix, levels.., merge])"""
-        ctx.set_option(hb.HG_OPT_STAGE_TIMING, 1)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        stages = np.array(ctx.read_stage_timings(min(n, hb.HG_TIMING_RING)), dtype=np.float64)
-        ctx.set_option(hb.HG_OPT_STAGE_TIMING, 0)
-        return (t1 - t0) * 1e3 / n, stages.mean(axis=0)
-
-    # the timed region: the library's default configuration (suffix and shared-block kernels overlap on two streams)
-    ms_per_step, st_timed = timed(args.steps)
+    # ---- the timed region: the library's default configuration, nothing but the calls between two synchronisations ----
+    ms_per_step = r.timed_region(args.steps)
+    # device-side duration of a call, step by step (median and minimum next to the mean)
+    ev_stats = r.per_step_events(args.steps)
+    ev_flushed = None
+    if args.flush_mib > 0:
+        fb = torch.zeros(args.flush_mib << 20, dtype=torch.uint8, device="cuda:0")
+        ev_flushed = r.per_step_events(args.steps, flush=fb)
+        del fb
     graph_ms = None
     if args.graph:
         # the same call captured once in a HIP graph on a side stream and replayed: no per-launch host work
         gs = torch.cuda.Stream()
         ctx.set_stream(gs)
         with torch.cuda.stream(gs):
-            step()
+            r.step()
         gs.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=gs):
-            step()
+            r.step()
         torch.cuda.synchronize()
         for _ in range(args.warmup):
             g.replay()
@@ -180,60 +455,26 @@ def main() -> int:
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         ctx.set_stream(None)
-    # per-kernel durations for the rooflines: the same K steps again with the kernels serialised on one stream, so
-    # that each duration is that kernel alone (when they overlap, each one's events also span the other's work)
-    serial_ms_per_step = None
-    st = st_timed
-    if args.overlap != 1:
-        ctx.set_option(hb.HG_OPT_OVERLAP, 1)
-        for _ in range(3):
-            step()
-        serial_ms_per_step, st = timed(args.steps)
-        ctx.set_option(hb.HG_OPT_OVERLAP, args.overlap)
+    # per-kernel durations for the rooflines: a second pass of K steps with the kernels serialised on one stream (when
+    # they overlap, each one's events also span the other's work) and the library's per-kernel events switched on
+    # (which also keeps the call on the separate kernels)
+    _, st_overlapped = r.staged(min(args.steps, 20)) if args.overlap != 1 else (None, None)
+    ctx.set_option(hb.HG_OPT_OVERLAP, 1)
+    for _ in range(3):
+        r.step()
+    serial_ms_per_step, st = r.staged(args.steps)
+    ctx.set_option(hb.HG_OPT_OVERLAP, args.overlap)
     nlev = len(dw.levels)
-    suffix_ms, level_ms, merge_ms = float(st[0]), [float(x) for x in st[1:1 + nlev]], float(st[1 + nlev])
+    kernels = kernel_table(w, st, nlev, args.fp8_kv)
 
-    # ---- algorithmic work per launch --------------------------------------------------------------------------
-    B, Hq, Hkv, D, G = w.B, w.Hq, w.Hkv, w.D, w.G
-    nq = w.nq
-    rows = B * nq * Hq
-    T = int(np.minimum(w.lengths, w.max_len).sum())
-    kv_elem = 1 if args.fp8_kv else 2
-    suffix_bytes = 2 * kv_elem * T * Hkv * D + rows * D * 2 + rows * (D + 1) * 4          # K+V rows, Q, partial (O, LSE)
-    level_flops, level_bytes = [], []
-    for lv in w.levels:
-        f = by = 0
-        for g in range(lv.Gn):
-            nk = int(lv.kv_off[g + 1] - lv.kv_off[g])
-            ns = int(lv.seq_off[g + 1] - lv.seq_off[g])
-            f += 4 * ns * nq * Hq * nk * D
-            by += 4 * nk * Hkv * D + ns * nq * Hq * D * 2 + ns * nq * Hq * (D + 1) * 4
-        level_flops.append(f)
-        level_bytes.append(by)
-    kernels = {"suffix": {"bound": "hbm", "ms": suffix_ms, "achieved": suffix_bytes / (suffix_ms * 1e-3) / 1e9 if suffix_ms else 0.0,
-                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "algorithmic": suffix_bytes}}
-    for i in range(nlev):
-        ms = level_ms[i]
-        tf = level_flops[i] / (ms * 1e-3) / 1e12 if ms else 0.0
-        gb = level_bytes[i] / (ms * 1e-3) / 1e9 if ms else 0.0
-        # a level is priced against the roofline that binds it: flops/byte above ~312 -> matrix cores, else HBM
-        mfma_bound = level_flops[i] / max(level_bytes[i], 1) >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-        kernels[f"prefix_level{i}"] = (
-            {"bound": "mfma", "ms": ms, "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "algorithmic": level_flops[i], "hbm_GBs": gb}
-            if mfma_bound else
-            {"bound": "hbm", "ms": ms, "achieved": gb, "peak": PEAK_HBM_GBS, "unit": "GB/s", "algorithmic": level_bytes[i], "TFLOPs": tf})
-    nparts_bytes = None  # merge: reads every partial once, writes bf16 O + LSE
-    kernels["merge"] = {"bound": "hbm", "ms": merge_ms, "unit": "GB/s", "peak": PEAK_HBM_GBS}
-    for k in kernels.values():
-        if "achieved" in k:
-            k["frac"] = k["achieved"] / k["peak"]
     dom_name = max((k for k in kernels if k != "merge"), key=lambda k: kernels[k]["ms"])
     dom = kernels[dom_name]
+    counters = stored_counters(dom_name, w.name)
     roofline = {"kernel": dom_name, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
-                "frac": dom["frac"], "traffic": MEASURED_TRAFFIC.get((dom_name, w.name)), "avg_launch_ms": dom["ms"],
-                "mfma_util": MEASURED_MFMA_UTIL.get((dom_name, w.name)),
-                "measured": "HIP events around the kernel on its stream, mean over the serialised pass of the same K steps"
-                            if serial_ms_per_step is not None else "HIP events around the kernel on its stream, mean over the timed region"}
+                "frac": dom["frac"], "traffic": None if counters is None else counters.get("traffic_bytes"),
+                "traffic_source": None if counters is None else counters.get("file"),
+                "avg_launch_ms": dom["ms"], "median_launch_ms": dom["ms_median"], "min_launch_ms": dom["ms_min"],
+                "measured": "HIP events around the kernel on its stream, over the serialised pass of the same K steps"}
 
     # ---- non-decomposed comparison ----------------------------------------------------------------------------
     naive_ms = None
@@ -281,8 +522,11 @@ def main() -> int:
     # ---- CPU oracle on a bounded sample: baseline figure + parity spot check of the timed configuration --------
     cpu = None
     parity = None
+    B, Hq, Hkv, nq = w.B, w.Hq, w.Hkv, w.nq
     if args.cpu_sample > 0:
         import oracle
+        r.step()                 # the outputs of the default configuration (the serialised pass ran last)
+        torch.cuda.synchronize()
         n = min(args.cpu_sample, B)
         seqs = np.unique(np.concatenate([np.linspace(0, B - 1, n).astype(np.int64),
                                          [int(np.argmin(w.lengths)), int(np.argmax(w.lengths))]])).astype(np.int32)
@@ -318,31 +562,55 @@ def main() -> int:
         ok = dO <= 1e-2 and dL <= 1e-3 and rel <= 1e-2
         parity["ok"] = bool(ok)
 
+    ceilings = measure_ceilings(hb, torch, ctx) if want_ceilings else None
+    shared_levels = [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels]
+    r.close()
+    del r, dw, O, L
+    torch.cuda.empty_cache()
+
+    # ---- the other configurations (their own default and serialised passes) ------------------------------------------
+    configs = None
+    if want_configs:
+        configs = []
+        csteps, cwarm = min(args.steps, 30), 5
+        for idx, P in ((2, None), (3, 1024), (3, 4096), (4, None), (5, None)):
+            t1 = time.time()
+            wc = wl.config(idx, P=P)
+            configs.append(measure_config(wc, args, hb, dev, torch, csteps, cwarm))
+            print(f"[bench] config {idx}{'' if P is None else f' P={P}'}: {configs[-1]['ms_per_step']:.4f} ms per call "
+                  f"({time.time() - t1:.1f}s)", file=sys.stderr, flush=True)
+            del wc
+
+    st_ms = [s["mean"] for s in st]
     out = {
         "metric": "decode-attn queries/s per layer (B=1024, 16K prefix); MFMA util + HBM GB/s",
         "value": B * nq / (ms_per_step * 1e-3),
         "unit": "queries/s per layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": D, "queries_per_sequence": nq,
-                   "shared_levels": [{"blocks": lv.Gn, "rows_per_block": lv.max_rows, "seqs_per_block": lv.max_seqs} for lv in w.levels],
+        "config": {"workload": w.name, "B": B, "Hq": Hq, "Hkv": Hkv, "D": w.D, "queries_per_sequence": nq,
+                   "shared_levels": shared_levels,
                    "suffix_len": [int(w.lengths.min()), int(w.lengths.max())], "suffix_tokens": int(w.T), "seed": w.seed,
                    "overlap_streams": args.overlap, "suffix_cache": (f"paged, {args.paged} rows per page" if args.paged else "packed rows") + (", 8-bit E4M3 codes" if args.fp8_kv else "")},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "ms_per_step_events": ev_stats,
+        "ms_per_step_events_flushed": ev_flushed,
         "kernels": kernels,
-        "stage_ms": {"suffix": suffix_ms, "prefix_levels": level_ms, "merge": merge_ms, "sum": float(st.sum()),
+        "stage_ms": {"suffix": st_ms[0], "prefix_levels": st_ms[1:1 + nlev], "merge": st_ms[1 + nlev], "sum": float(sum(st_ms)),
                      "ms_per_step_serialised": serial_ms_per_step},
-        "stage_ms_timed_region": {"suffix": float(st_timed[0]), "prefix_levels": [float(x) for x in st_timed[1:1 + nlev]],
-                                  "merge": float(st_timed[1 + nlev]), "note": "kernels overlap: each span includes the other's work"},
+        "stage_ms_overlapped": None if st_overlapped is None else {
+            "suffix": st_overlapped[0]["mean"], "prefix_levels": [s["mean"] for s in st_overlapped[1:1 + nlev]],
+            "merge": st_overlapped[1 + nlev]["mean"], "note": "kernels side by side: each span includes the other's work"},
         "naive": None if naive_ms is None else {"ms_per_step": naive_ms, "queries_per_s": B * nq / (naive_ms * 1e-3),
                                                  "speedup_hydragen_over_naive": naive_ms / ms_per_step},
         "kv_append_ms": append_ms,
         "graph_ms_per_step": graph_ms,
         "parity": parity,
+        "ceilings": ceilings,
+        "configs": configs,
     }
     print(json.dumps(out))
-    ctx.close()
     if parity is not None and not parity["ok"]:
         print("bench.py: parity spot check FAILED", file=sys.stderr)
         return 1

@@ -293,31 +293,6 @@ int hg_naive_attn(hg_ctx* ctx, const void* Q, int n_levels, const hg_level* leve
  */
 int hg_read_stage_timings(hg_ctx* ctx, float* ms, int n_calls);
 
-/*
- * Host-only views of the library's work partitioning, for tests and tuning (no device is touched, no context needed).
- *
- * hg_debug_wide_plan: the partition that the persistent 256-row shared-block kernel would use for a level of n_blocks
- * blocks of at most max_rows keys and max_seqs sequences, Hkv KV heads, rows_per_seq query rows per sequence and KV
- * head (queries per sequence x query heads per KV head), at most max_parts partial results per row, on slots_per_xcd
- * CUs of each of the 8 XCDs.  Fills out[9] = { stages per column (32 keys each), columns, row groups, workgroups per
- * team, slots, teams per XCD, stages per team, partial results per row, mode } and returns 1, or returns 0 if the level
- * does not fit.  With n_c stages per column, C columns and N = 8 * teams per XCD teams, team t walks the flattened
- * (column, stage) positions
- *   mode 0:         [t * quota, min((t+1) * quota, C * n_c)); a column cut by such a range yields one partial result
- *                   per piece, numbered t - floor(column * n_c / quota);
- *   mode 1, C <= N: column c = floor(t * C / N) belongs to the teams ceil(c * N / C) .. ceil((c+1) * N / C) - 1; the
- *                   i-th of its n teams walks its stages [floor(i * n_c / n), floor((i+1) * n_c / n)), part i;
- *   mode 1, C > N:  the whole columns floor(t * C / N) .. floor((t+1) * C / N) - 1, part 0.
- *
- * hg_debug_suffix_plan: the suffix kernel and chunking chosen with default options for B sequences of at most max_len
- * suffix rows, nq queries each, Hq / Hkv heads of dimension D (page_size > 0: paged cache).  Fills out[4] = { keys per
- * work item, work items per row (= partial results), 1 if the matrix-core kernel runs, query heads per vector-ALU
- * work item } and returns 1, or 0 on invalid arguments.
- */
-int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts,
-                       int slots_per_xcd, int out[9]);
-int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int page_size, int out[4]);
-
 const char* hg_strerror(int code);
 
 #ifdef __cplusplus

@@ -30,13 +30,13 @@ HG_TIMING_RING, HG_MAX_STAGES = 128, HG_MAX_LEVELS + 2
 # HYDRAGEN_LIB selects another build of the same library (e.g. one compiled with extra flags)
 LIB_PATH = os.environ.get("HYDRAGEN_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhydragen.so")
 
-# every symbol include/hydragen.h declares
+# every symbol include/hydragen.h and include/hydragen_debug.h declare
 EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
     "hg_debug_wide_plan", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
-    "hg_hydragen_attn_static",
+    "hg_hydragen_attn_static", "hg_debug_mfma_loop", "hg_debug_stream_read",
 )
 
 
@@ -118,6 +118,10 @@ def lib() -> ctypes.CDLL:
         L.hg_debug_wide_plan.restype = ci
         L.hg_debug_suffix_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
         L.hg_debug_suffix_plan.restype = ci
+        L.hg_debug_mfma_loop.argtypes = [vp, ci, ci, vp, vp]
+        L.hg_debug_mfma_loop.restype = ci
+        L.hg_debug_stream_read.argtypes = [vp, vp, cs, vp]
+        L.hg_debug_stream_read.restype = ci
         L.hg_read_stage_timings.argtypes = [vp, ctypes.POINTER(cf), ci]
         L.hg_read_stage_timings.restype = ci
         L.hg_strerror.argtypes = [ci]
@@ -468,3 +472,17 @@ def hg_debug_suffix_plan(B: int, nq: int, Hq: int, Hkv: int, D: int, max_len: in
     if not lib().hg_debug_suffix_plan(B, nq, Hq, Hkv, D, max_len, page_size, out):
         return None
     return dict(zip(("chunk", "nchunks", "mfma", "gt"), list(out)))
+
+
+def hg_debug_mfma_loop(ctx: Context, random_operands: bool, iters: int, clocks: torch.Tensor, sink: torch.Tensor) -> None:
+    """Enqueue the register-only matrix-instruction loop (see include/hydragen_debug.h); clocks: int64[2] on the device."""
+    _want(clocks, torch.int64, (2,), "clocks"); _want(sink, torch.float32, (1,), "sink")
+    _check(lib().hg_debug_mfma_loop(ctx.h, int(bool(random_operands)), iters, _p(clocks), _p(sink)), "hg_debug_mfma_loop")
+
+
+def hg_debug_stream_read(ctx: Context, src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Enqueue one streaming read of the whole of `src` (see include/hydragen_debug.h)."""
+    _want(sink, torch.float32, (1,), "sink")
+    if not src.is_cuda or not src.is_contiguous():
+        raise TypeError("src: need a contiguous device tensor")
+    _check(lib().hg_debug_stream_read(ctx.h, _p(src), src.numel() * src.element_size(), _p(sink)), "hg_debug_stream_read")

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhydragen.so")
-SOURCES = ["api.hip", "prefix.hip", "prefix_wide.hip", "decode.hip", "merge.hip", "kvcache.hip", "decode_mfma.hip", "fused_small.hip"]
+SOURCES = ["api.hip", "prefix.hip", "prefix_wide.hip", "decode.hip", "merge.hip", "kvcache.hip", "decode_mfma.hip", "fused_small.hip", "ceilings.hip"]
 
 # packed fp32 VALU forms are switched off for every device compile of this library
 HIPCC_FLAGS = [
@@ -63,7 +63,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "hydragen.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", h) for h in ("hydragen.h", "hydragen_debug.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -6,6 +6,7 @@
 #include <new>
 
 #include "hg_internal.h"
+#include "hydragen_debug.h"
 
 struct hg_ctx {
     int device;
@@ -1055,6 +1056,18 @@ int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int
     const SuffixPlan p = plan_suffix(&c, max_len, Hq / Hkv, B, nq, Hkv, D, page_size > 0, page_size > 0 ? 32 * page_size : 1 << 30);
     out[0] = p.chunk; out[1] = p.nchunks; out[2] = p.mfma ? 1 : 0; out[3] = p.gt;
     return 1;
+}
+
+int hg_debug_mfma_loop(hg_ctx* c, int random_operands, int iters, unsigned long long* clocks, float* sink) {
+    if (!c || iters < 1 || !clocks || !sink) return HG_ERR_INVALID_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    return hip_rc(hg::launch_mfma_loop(iters, random_operands ? 1 : 0, clocks, sink, c->stream));
+}
+
+int hg_debug_stream_read(hg_ctx* c, const void* src, size_t bytes, float* sink) {
+    if (!c || !src || !sink || bytes < 16 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return HG_ERR_INVALID_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    return hip_rc(hg::launch_stream_read(src, bytes, sink, c->stream));
 }
 
 const char* hg_strerror(int code) {

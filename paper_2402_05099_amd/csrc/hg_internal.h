@@ -152,6 +152,8 @@ hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s);   // matrix-core per-sequence kernel (8-bit rows: D = 128 only)
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);
 hipError_t launch_fused_small(const SmallArgs& a, int D, hipStream_t s);
+hipError_t launch_mfma_loop(int iters, int random_operands, unsigned long long* clocks, float* sink, hipStream_t s);
+hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
 

@@ -19,9 +19,18 @@ def lib():
 
 
 def declared_functions():
+    names = set()
+    for header in ("hydragen.h", "hydragen_debug.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(hg_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_attention_header_declares_no_debug_entry_point():
     text = open(os.path.join(ROOT, "include", "hydragen.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hg_[a-z0-9_]+)\s*\(", text)))
+    assert not re.findall(r"\bhg_debug_[a-z0-9_]+\s*\(", text)
 
 
 def test_header_and_binding_agree():
