@@ -310,6 +310,57 @@ def power_table(args, hb, dev, wl, torch):
     return 0
 
 
+def wide_timeline(args, hb, dev, wl, torch):
+    """Phase time stamps of the persistent shared-block kernel on every shared level of the workload, from a library
+    built with -DHG_TRACE (python -m paper_2402_05099_amd.build --out <lib> -DHG_TRACE; HYDRAGEN_LIB=<lib>)."""
+    import ctypes
+    import numpy as np
+    L = hb.lib()
+    if not hasattr(L, "hg_debug_read_wide_trace"):
+        print("bench.py --wide-timeline needs a -DHG_TRACE build of the library (see HYDRAGEN_LIB)", file=sys.stderr)
+        return 2
+    L.hg_debug_read_wide_trace.argtypes = [ctypes.c_void_p]
+    w = wl.config(args.config, P=args.prefix or None)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=args.parts)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, 2)
+    O = torch.empty(dw.lead + (dw.D,), dtype=torch.float32, device="cuda:0")
+    LS = torch.empty(dw.lead, dtype=torch.float32, device="cuda:0")
+    print(f"# prefix_kernel_wide, phase time stamps per workgroup (100 MHz counter; us from the first workgroup's entry), {w.name}")
+    for li, lv in enumerate(dw.levels):
+        plan = hb.hg_debug_wide_plan(lv.n_blocks, lv.max_rows, lv.max_seqs if lv.kv_off is not None else dw.B, dw.Hkv,
+                                     dw.nq * (dw.Hq // dw.Hkv), args.parts, 32)
+        for _ in range(3):
+            hb.hg_prefix_attn_grouped(ctx, dw.Q, lv, O, LS, dw.scale)
+        torch.cuda.synchronize()
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, lv, O, LS, dw.scale)
+        buf = np.zeros(256 * 24, dtype=np.uint64)
+        assert L.hg_debug_read_wide_trace(buf.ctypes.data_as(ctypes.c_void_p)) == 0
+        t = buf.reshape(256, 24).astype(np.float64)[:8 * plan["slots"]]
+        t0 = t[:, 0].min()
+        print(f"level {li}: plan {plan}")
+        print(f"  kernel span {(t[:, 15].max() - t0) / 100:.1f} us; workgroups leave between {(t[:, 15].min() - t0) / 100:.1f} and {(t[:, 15].max() - t0) / 100:.1f} us")
+        for p in range(3):
+            b = 1 + 4 * p
+            ok = t[:, b + 3] > t[:, b]
+            if not ok.any():
+                continue
+            a_, b_, c_, d_ = (t[ok, b + k] for k in range(4))
+            cyc = t[ok, 16 + p]
+            print(f"  piece {p}: {int(ok.sum())} workgroups; entry at {(a_ - t0).mean() / 100:.1f}; wait + first scores {(b_ - a_).mean() / 100:.2f} "
+                  f"(max {(b_ - a_).max() / 100:.2f}); steps {(c_ - b_).mean() / 100:.2f} (max {(c_ - b_).max() / 100:.2f}) = {cyc.mean():.0f} cycles "
+                  f"at {cyc.mean() / ((c_ - b_).mean() * 10):.2f} GHz; next Q request + result stores {(d_ - c_).mean() / 100:.2f} (max {(d_ - c_).max() / 100:.2f})")
+        ok = t[:, 22] > t[:, 19]
+        if ok.any():
+            x = t[ok]
+            print(f"  boundary between pieces 0 and 1 ({int(ok.sum())} workgroups): next piece looked up {(x[:, 19] - x[:, 3]).mean() / 100:.2f}; "
+                  f"Q requested {(x[:, 20] - x[:, 19]).mean() / 100:.2f}; results stored {(x[:, 4] - x[:, 20]).mean() / 100:.2f}; "
+                  f"wait for Q {(x[:, 21] - x[:, 5]).mean() / 100:.2f}; barrier {(x[:, 22] - x[:, 21]).mean() / 100:.2f}; "
+                  f"first scores {(x[:, 6] - x[:, 22]).mean() / 100:.2f}")
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -339,6 +390,7 @@ def main() -> int:
     ap.add_argument("--flush-mib", type=int, default=0, help="per-step events pass: write a buffer of this many MiB between steps (more than the 256 MiB last-level cache), reported as ms_per_step_events_flushed")
     ap.add_argument("--extra-configs", type=int, default=-1, help="1: also measure configs 2, 3 at P=1024/4096, 4 and 5 (`configs`); default: only in the plain headline run")
     ap.add_argument("--ceilings", type=int, default=-1, help="1: also measure the matrix-instruction and streaming-read ceilings (`ceilings`); default: only in the plain headline run")
+    ap.add_argument("--wide-timeline", action="store_true", help="separate mode: per-workgroup phase time stamps of the persistent shared-block kernel (needs a -DHG_TRACE build of the library selected with HYDRAGEN_LIB); prints a text table")
     ap.add_argument("--power-table", action="store_true", help="separate mode: board power while each kernel of the workload is repeated for three seconds; prints a text table")
     args = ap.parse_args()
 
@@ -359,6 +411,8 @@ def main() -> int:
     hb.lib()  # fail loudly if the HIP library is missing
     if args.power_table:
         return power_table(args, hb, dev, wl, torch)
+    if args.wide_timeline:
+        return wide_timeline(args, hb, dev, wl, torch)
 
     plain = (args.config == 3 and not (args.prefix or args.batch or args.suffix_len or args.paged or args.fp8_kv or args.nq > 1
                                        or args.splits or args.overlap or args.suffix_chunk or args.prefix_kernel

@@ -45,8 +45,13 @@
  *     hg_merge is unaffected (it takes a row count).
  *   - scale <= 0 selects 1/sqrt(D) (Eq. 1).
  *   - Supported: D in {64, 128}; Hq % Hkv == 0; B*nq*Hq*D < 2^31; rows*Hkv*D < 2^31 per tensor.
- *   - Every call returns HG_OK or an error code; on error nothing is enqueued
- *     and outputs are untouched.  No C++ exception crosses this boundary.
+ *   - Every call returns HG_OK or an error code.  Arguments, shapes, sizes and
+ *     the workspace are checked before anything is enqueued: on those errors
+ *     (every code but HG_ERR_HIP) nothing is enqueued and outputs are untouched.
+ *     HG_ERR_HIP reports a failure of the HIP runtime itself, possibly after
+ *     part of the call's work was enqueued: outputs are then undefined, and the
+ *     library's second stream has been joined back to the context's stream.
+ *     No C++ exception crosses this boundary.
  *   - Calls on one context must not overlap in time from several host threads.
  */
 #ifndef HYDRAGEN_H
@@ -116,8 +121,8 @@ int hg_prefix_attn(hg_ctx* ctx, const void* Q, const void* Kp, const void* Vp,
  * Block g owns KV rows [kv_off[g], kv_off[g+1]) and is attended to by the contiguous sequences
  * [seq_off[g], seq_off[g+1]) (sequences are in tree order).  kv_off/seq_off are DEVICE int32[n_blocks+1],
  * non-decreasing.  max_rows / max_seqs are host upper bounds on rows and sequences per block; a block
- * exceeding them is truncated.  A block shorter than 32 rows is read together with the rows stored just below it
- * (they get weight zero): those rows must hold finite values, which blocks stored back to back guarantee.
+ * exceeding them is truncated.  Rows of K/V that are no block's keys (the truncated tail of a block, rows before the
+ * first block) may hold anything, NaN included: the kernels may read them but never give them a weight.
  * With n_blocks == 1 both arrays may be NULL: the block is then rows
  * [0, max_rows) shared by sequences [0, B).  Sequences not covered by any block get O = 0, LSE = -inf.
  */

@@ -9,7 +9,7 @@ be checked by eye against the definition it states:
     step adds the newest token's): the nq new rows of sequence b become suffix rows length_b .. length_b + nq - 1,
     rows at or above the capacity are dropped, and the length grows by the number of rows kept.
 
-Pinned in tests/test_oracle_pins.py by hand-typed tiny cases and by round trips through the scatter of the input
+Pinned in tests/test_kvcache_pins.py by hand-typed tiny cases and by round trips through the scatter of the input
 generator (which is independent code).
 """
 from __future__ import annotations

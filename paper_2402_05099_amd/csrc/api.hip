@@ -493,6 +493,8 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     const int ns = plan.ns;
     hipStream_t s = c->stream;
     if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
+    if (!plan.wide && (int64_t)lv.n_blocks * ns * Hkv * ceil_div(lv.max_seqs * nq * (Hq / Hkv), kPrefixRowsNarrow) >= (1LL << 28))
+        return HG_ERR_UNSUPPORTED;      // (checked before anything is enqueued)
     if (ns == 1) {
         if (lv.seq_off) {
             rc = fill_empty(O, o_dtype, LSE, rows, D, s);
@@ -756,6 +758,16 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
         }
     }
     if (has_suffix && !sp.mfma && sp.chunk > max_chunk) return HG_ERR_WORKSPACE;
+    // every size limit of the launches below is checked here, before anything is enqueued
+    for (int i = 0; i < nlev; ++i) {
+        if (plan[i].wide) continue;
+        const int64_t tiles = (int64_t)lv[i].n_blocks * ns[i] * Hkv * ceil_div(lv[i].max_seqs * nq * G, kPrefixRowsNarrow);
+        if (tiles >= (1LL << 28)) return HG_ERR_UNSUPPORTED;
+    }
+    if (has_suffix && sp.mfma) {
+        const int tile_rows = (nq * G <= 16 && c->opt_suffix_tile != 32) ? 16 : 32;
+        if ((int64_t)B * sp.nchunks * ceil_div(nq * G, tile_rows) * Hkv >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+    }
     const int np = total_parts();
     hipStream_t s = c->stream;
     if (np == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
@@ -820,16 +832,26 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     // for suffix wavefronts on their CUs and go second unless HG_OPT_OVERLAP = 2 asks for them first.
     bool any_wide = false;
     for (int i = 0; i < nlev; ++i) any_wide = any_wide || plan[i].wide;
+    // A launch that fails here (a HIP runtime error: the sizes were checked above) leaves work enqueued and the
+    // second stream forked: the fork is still joined before the error is returned, so that a stream capture in
+    // progress stays valid and nothing runs behind the caller's back on the second stream.
+    auto fail = [&](int code) -> int {
+        if (overlap) {
+            (void)hipEventRecord(c->ev_join, c->aux);
+            (void)hipStreamWaitEvent(s, c->ev_join, 0);
+        }
+        return code;
+    };
     if (c->opt_overlap == 2 || (c->opt_overlap == 0 && any_wide)) {
         rc = enqueue_levels();
-        if (rc) return rc;
+        if (rc) return fail(rc);
         rc = enqueue_suffix();
-        if (rc) return rc;
+        if (rc) return fail(rc);
     } else {
         rc = enqueue_suffix();
-        if (rc) return rc;
+        if (rc) return fail(rc);
         rc = enqueue_levels();
-        if (rc) return rc;
+        if (rc) return fail(rc);
     }
     if (overlap && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HG_ERR_HIP;
     if (!mark(nlev + 1, 0, s)) return HG_ERR_HIP;
@@ -983,6 +1005,11 @@ int hg_naive_attn(hg_ctx* c, const void* Q, int n_levels, const hg_level* levels
         };
         while (parts_for(chunk) > cap && chunk < (1 << 29)) chunk *= 2;
         if (parts_for(chunk) > cap) return HG_ERR_WORKSPACE;
+        {   // item counts of every launch below, checked before anything is enqueued
+            const int tile_rows = (nq * G <= 16 && c->opt_suffix_tile != 32) ? 16 : 32;
+            const int64_t per = (int64_t)B * ceil_div(nq * G, tile_rows) * Hkv;
+            if (per * parts_for(chunk) >= (1LL << 31)) return HG_ERR_UNSUPPORTED;
+        }
         int first = 0;
         for (int i = 0; i < n_levels; ++i) {
             if (lv[i].max_rows <= 0) continue;

@@ -205,6 +205,58 @@ def test_grouped_level_with_uncovered_sequences_and_unequal_blocks():
     ctx.close()
 
 
+@pytest.mark.parametrize("kernel", [1, 2], ids=["rows128", "rows256"])
+def test_shared_blocks_ignore_rows_that_are_nobodys_keys(kernel):
+    """Blocks truncated by max_rows leave rows in the level's tensors that are no block's keys; here they hold NaN,
+    as do the rows around the blocks.  The kernels re-read a window of 32 rows around a short block (the rows just
+    below it, the rows past a range that ends before row 32 of the tensor): none of that may reach a result."""
+    say(f"nobody's keys kernel={kernel}")
+    B, Hq, Hkv, D = 300, 4, 2, 128
+    max_rows = 20
+    first = 7                               # rows before the first block
+    stored = [50, 5, 45]                    # rows each block owns in the tensors
+    used = [min(n, max_rows) for n in stored]      # ... of which these count: 20, 5, 20
+    w = wl.make_workload("truncated", 61, B, Hq, Hkv, D, [(1, sum(used), B)], 0, 33)
+    lv = w.levels[0]
+    seq_off = np.array([0, 140, 150, 300], np.int32)
+    lv.kv_off = np.concatenate([[0], np.cumsum(used)]).astype(np.int32)     # the oracle's view: the used rows, back to back
+    lv.seq_off = seq_off
+    Oref, Lref = oracle.attention(w)
+    Op, Lp = oracle.attention(w, levels=[0], suffix=False)
+    # the device's view: NaN rows before the first block, and every block followed by its unused rows, all NaN
+    Kd = np.full((first + sum(stored), Hkv, D), 0x7FC0, np.uint16)
+    Vd = np.full((first + sum(stored), Hkv, D), 0x7FC0, np.uint16)
+    kv_off_d = (first + np.concatenate([[0], np.cumsum(stored)])).astype(np.int32)
+    for g in range(3):
+        Kd[kv_off_d[g]: kv_off_d[g] + used[g]] = lv.K[lv.kv_off[g]: lv.kv_off[g + 1]]
+        Vd[kv_off_d[g]: kv_off_d[g] + used[g]] = lv.V[lv.kv_off[g]: lv.kv_off[g + 1]]
+    dw = dev.to_device(w)
+    level = hb.Level(K=dev.bf16_tensor(Kd, "cuda:0"), V=dev.bf16_tensor(Vd, "cuda:0"), n_blocks=3,
+                     kv_off=torch.from_numpy(kv_off_d).cuda(), seq_off=torch.from_numpy(seq_off).cuda(), max_rows=max_rows, max_seqs=150)
+    ctx = dev.make_context(dw, parts=8)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
+    for splits in (0, 2):
+        ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
+        O, L, intact = outputs(dw)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, level, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Op, Lp, f"truncated blocks kernel={kernel} splits={splits}")
+        O, L, intact = outputs(dw)
+        hb.hg_hydragen_attn(ctx, dw.Q, [level], dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"truncated blocks, fused kernel={kernel} splits={splits}")
+    O, L, intact = outputs(dw)
+    hb.hg_naive_attn(ctx, dw.Q, [level], dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+    assert intact()
+    check(to_np(O), to_np(L), Oref, Lref, f"truncated blocks, comparison call kernel={kernel}")
+    ctx.set_option(hb.HG_OPT_FUSED_KERNEL, 2)
+    O, L, intact = outputs(dw)
+    hb.hg_hydragen_attn(ctx, dw.Q, [level], dw.Ks, dw.Vs, dw.offsets, dw.lengths, dw.max_len, O, L, dw.scale)
+    assert intact()
+    check(to_np(O), to_np(L), Oref, Lref, f"truncated blocks, single launch")
+    ctx.close()
+
+
 @pytest.mark.parametrize("name,B,Hq,Hkv,P,parts", [
     ("three_tiles", 75, 8, 1, 1000, 8),      # 600 query rows per KV head: teams of 3 workgroups, ragged last tile and stage
     ("three_tiles_two_parts", 75, 8, 1, 1000, 2),   # workspace for two partial results only: longer ranges per team

@@ -296,13 +296,12 @@ def test_tree_three_way_merge_equals_full():
     assert np.allclose(Lm, Lf, rtol=0, atol=1e-12)
 
 
-def paper_two_way_combine(out1, lse1, out2, lse2):
-    """The two-part combine as App. B states it (max LSE, two adjust factors, new denominator), in numpy fp64."""
-    mx = np.maximum(lse1, lse2)
-    f1 = np.exp(lse1 - mx)
-    f2 = np.exp(lse2 - mx)
-    den = f1 + f2
-    return (out1 * f1[..., None] + out2 * f2[..., None]) / den[..., None]
+def sigmoid_two_way_combine(out1, lse1, out2, lse2):
+    """Two parts merged through the logistic function, a form of Eq. 5 derived independently of the oracle's code: the
+    weight of part 1 is e^{lse1} / (e^{lse1} + e^{lse2}) = 1 / (1 + e^{lse2 - lse1}), that of part 2 its complement."""
+    with np.errstate(over="ignore"):
+        w1 = 1.0 / (1.0 + np.exp(lse2 - lse1))
+    return out1 * w1[..., None] + out2 * (1.0 - w1)[..., None]
 
 
 def test_merge_against_two_way_combine_and_nesting():
@@ -311,7 +310,7 @@ def test_merge_against_two_way_combine_and_nesting():
     Os = [rng.standard_normal((rows, D)) for _ in range(4)]
     Ls = [rng.standard_normal(rows) * 5 for _ in range(4)]
     O2, L2 = oracle.merge(Os[:2], Ls[:2])
-    assert np.allclose(O2, paper_two_way_combine(Os[0], Ls[0], Os[1], Ls[1]), rtol=0, atol=1e-13)
+    assert np.allclose(O2, sigmoid_two_way_combine(Os[0], Ls[0], Os[1], Ls[1]), rtol=0, atol=1e-13)
     assert np.allclose(L2, np.logaddexp(Ls[0], Ls[1]), rtol=0, atol=1e-13)
     # Eq. 5 literally (no max subtraction) on moderate LSEs
     w = [np.exp(l) for l in Ls]
