@@ -334,12 +334,16 @@ def wide_timeline(args, hb, dev, wl, torch):
             hb.hg_prefix_attn_grouped(ctx, dw.Q, lv, O, LS, dw.scale)
         torch.cuda.synchronize()
         hb.hg_prefix_attn_grouped(ctx, dw.Q, lv, O, LS, dw.scale)
-        buf = np.zeros(256 * 24, dtype=np.uint64)
+        buf = np.zeros(256 * 32, dtype=np.uint64)
         assert L.hg_debug_read_wide_trace(buf.ctypes.data_as(ctypes.c_void_p)) == 0
-        t = buf.reshape(256, 24).astype(np.float64)[:8 * plan["slots"]]
+        t = buf.reshape(256, 32).astype(np.float64)[:8 * plan["slots"]]
         t0 = t[:, 0].min()
         print(f"level {li}: plan {plan}")
-        print(f"  kernel span {(t[:, 15].max() - t0) / 100:.1f} us; workgroups leave between {(t[:, 15].min() - t0) / 100:.1f} and {(t[:, 15].max() - t0) / 100:.1f} us")
+        print(f"  kernel span {(t[:, 15].max() - t0) / 100:.1f} us; workgroups start between 0 and {(t[:, 0].max() - t0) / 100:.1f} us (mean {(t[:, 0] - t0).mean() / 100:.2f}) "
+              f"and leave between {(t[:, 15].min() - t0) / 100:.1f} and {(t[:, 15].max() - t0) / 100:.1f} us; from a workgroup's start to its first piece's entry "
+              f"{(t[:, 1] - t[:, 0]).mean() / 100:.2f} (max {(t[:, 1] - t[:, 0]).max() / 100:.2f}): first piece looked up {(t[:, 24] - t[:, 0]).mean() / 100:.2f}, "
+              f"Q requested {(t[:, 25] - t[:, 24]).mean() / 100:.2f}, copy cursor set {(t[:, 26] - t[:, 25]).mean() / 100:.2f}, first stage's copies issued "
+              f"{(t[:, 27] - t[:, 26]).mean() / 100:.2f}, six more stages {(t[:, 1] - t[:, 27]).mean() / 100:.2f}")
         for p in range(3):
             b = 1 + 4 * p
             ok = t[:, b + 3] > t[:, b]
@@ -347,9 +351,10 @@ def wide_timeline(args, hb, dev, wl, torch):
                 continue
             a_, b_, c_, d_ = (t[ok, b + k] for k in range(4))
             cyc = t[ok, 16 + p]
+            nst = t[ok, 23 if p == 2 else 13 + p]
             print(f"  piece {p}: {int(ok.sum())} workgroups; entry at {(a_ - t0).mean() / 100:.1f}; wait + first scores {(b_ - a_).mean() / 100:.2f} "
                   f"(max {(b_ - a_).max() / 100:.2f}); steps {(c_ - b_).mean() / 100:.2f} (max {(c_ - b_).max() / 100:.2f}) = {cyc.mean():.0f} cycles "
-                  f"at {cyc.mean() / ((c_ - b_).mean() * 10):.2f} GHz; next Q request + result stores {(d_ - c_).mean() / 100:.2f} (max {(d_ - c_).max() / 100:.2f})")
+                  f"at {cyc.mean() / ((c_ - b_).mean() * 10):.2f} GHz, {nst.mean():.1f} stages, {cyc.sum() / nst.sum():.0f} cycles per stage; next Q request + result stores {(d_ - c_).mean() / 100:.2f} (max {(d_ - c_).max() / 100:.2f})")
         ok = t[:, 22] > t[:, 19]
         if ok.any():
             x = t[ok]

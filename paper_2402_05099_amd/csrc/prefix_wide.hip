@@ -99,17 +99,21 @@ extern __shared__ __attribute__((aligned(1024))) unsigned char wide_smem[];
 // stores the 100 MHz real-time counter at kernel entry (slot 0) and exit (slot 15) and, for its first three pieces
 // p, at 1 + 4p + {0 piece entry, 1 first scores done, 2 main loop done, 3 results stored}; slots 16 + p hold the
 // shader-clock cycles of piece p's main loop; slots 19 .. 22 split the boundary between pieces 0 and 1 (next piece
-// looked up, its Q requested, Q landed, barrier passed).  hg_debug_read_wide_trace copies the table to the host.
+// looked up, its Q requested, Q landed, barrier passed); slots 13, 14 and 23 hold the number of stages of pieces 0, 1
+// and 2 (a count, not a time); slots 24 .. 27 split the start of the kernel (first piece looked up, its Q requested,
+// copy cursor set, first stage's copies issued).  hg_debug_read_wide_trace copies the table to the host.
 #ifdef HG_TRACE
-constexpr int kTraceSlots = 24;
+constexpr int kTraceSlots = 32;
 __device__ unsigned long long hg_wide_trace[256 * kTraceSlots];
 #define HG_T(slot) do { if (threadIdx.x == 0) hg_wide_trace[blockIdx.x * kTraceSlots + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #define HG_TP(piece, k) do { if ((piece) < 3) HG_T(1 + 4 * (piece) + (k)); } while (0)
+#define HG_TN(piece, n) do { if (threadIdx.x == 0 && (piece) < 3) hg_wide_trace[blockIdx.x * kTraceSlots + ((piece) == 2 ? 23 : 13 + (piece))] = (unsigned long long)(n); } while (0)
 #define HG_TC_BEGIN() const unsigned long long hg_tc0 = __builtin_amdgcn_s_memtime()
 #define HG_TC_END(piece) do { if (threadIdx.x == 0 && (piece) < 3) hg_wide_trace[blockIdx.x * kTraceSlots + 16 + (piece)] = __builtin_amdgcn_s_memtime() - hg_tc0; } while (0)
 #else
 #define HG_T(slot) do { } while (0)
 #define HG_TP(piece, k) do { } while (0)
+#define HG_TN(piece, n) do { } while (0)
 #define HG_TC_BEGIN() do { } while (0)
 #define HG_TC_END(piece) do { } while (0)
 #endif
@@ -480,16 +484,23 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
     {
         const kargs_ptr k = kargs();       // one look at the arguments for everything up to the first copies
         if (!next_piece(k)) return;
+        HG_T(24);
         load_q(k, row_ctx(k, pc));
+        HG_T(25);
         cursor_next_piece(k);               // finds at least the piece next_piece() found
+        HG_T(26);
     }
     int qkind = kQFirst;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue_stage(s);
+    for (int s = 0; s < NS - 1; ++s) {
+        issue_stage(s);
+        if (s == 0) HG_T(27);
+    }
     int piece_no = 0;
 
     for (;;) {
         HG_TP(piece_no, 0);
+        HG_TN(piece_no, pc.nst);
         // ---- piece prologue ---------------------------------------------------------------------------------------------
         // Q and the stream's next stages have landed, for everyone
         wait_q(qkind);
@@ -666,7 +677,7 @@ __global__ __launch_bounds__(64 * NW, 1) void prefix_kernel_wide(PrefixArgs a) {
 
 #ifdef HG_TRACE
 }  // namespace hg
-// Copies the phase time stamps of the most recent prefix_kernel_wide launches to `out` (HOST, 256 * 24 values) after
+// Copies the phase time stamps of the most recent prefix_kernel_wide launches to `out` (HOST, 256 * 32 values) after
 // synchronising the device; present only in a -DHG_TRACE build.
 extern "C" int hg_debug_read_wide_trace(unsigned long long* out) {
     if (hipDeviceSynchronize() != hipSuccess) return HG_ERR_HIP;
