@@ -375,6 +375,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="config 6: batch size")
     ap.add_argument("--suffix-len", type=int, default=0, help="config 6: suffix length of every sequence")
     ap.add_argument("--prefix", type=int, default=0, help="override the level-0 prefix length")
+    ap.add_argument("--head-dim", type=int, default=0, help="head dimension of configs 2..6 (128; 64 is a variant, never the headline)")
     ap.add_argument("--naive-steps", type=int, default=3)
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--splits", type=int, default=0)
@@ -419,7 +420,7 @@ def main() -> int:
     if args.wide_timeline:
         return wide_timeline(args, hb, dev, wl, torch)
 
-    plain = (args.config == 3 and not (args.prefix or args.batch or args.suffix_len or args.paged or args.fp8_kv or args.nq > 1
+    plain = (args.config == 3 and not (args.head_dim or args.prefix or args.batch or args.suffix_len or args.paged or args.fp8_kv or args.nq > 1
                                        or args.splits or args.overlap or args.suffix_chunk or args.prefix_kernel
                                        or args.suffix_kernel or args.fused_kernel or args.wide_slots))
     want_configs = plain if args.extra_configs < 0 else bool(args.extra_configs)
@@ -427,7 +428,7 @@ def main() -> int:
 
     t0 = time.time()
     variant = {"nq": args.nq} if args.nq > 1 else {}
-    w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None, **variant)
+    w = wl.config(args.config, P=args.prefix or None, B=args.batch or None, L=args.suffix_len or None, D=args.head_dim or None, **variant)
 
     kv = None
     f8 = None          # packed 8-bit cache

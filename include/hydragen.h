@@ -79,7 +79,7 @@ enum {
     HG_OPT_OVERLAP = 3,       /* fused call: 0 shared-block and suffix kernels overlap on two streams, 1 one stream, 2 two streams with the shared-block kernels enqueued first */
     HG_OPT_NAIVE_CHUNK = 4,   /* keys per work item of the non-decomposed comparison kernel */
     HG_OPT_STAGE_TIMING = 5,  /* 1: hg_hydragen_attn brackets each of its kernels with timing events */
-    HG_OPT_PREFIX_KERNEL = 6, /* shared-block kernel: 0 automatic (persistent 256-row kernel for D = 128 blocks with more than 128 query rows, else the 128-row kernel), 1 always 128-row, 2 256-row wherever D = 128 */
+    HG_OPT_PREFIX_KERNEL = 6, /* shared-block kernel: 0 automatic (persistent 256-row kernel for blocks with more than 128 query rows, else the 128-row kernel), 1 always 128-row, 2 always 256-row */
     HG_OPT_WIDE_SLOTS = 7,    /* CUs per XCD (1..32) that the persistent 256-row kernel occupies; 0 = automatic */
     HG_OPT_NUM_QUERIES = 8,   /* queries per sequence, 1..64 (default 1 = decode); see "Several queries per sequence" below */
     HG_OPT_SUFFIX_ITEMS_PER_WAVE = 10, /* matrix-core suffix kernel: consecutive work items one wavefront takes (1..1024; 0 = automatic) */

@@ -16,8 +16,9 @@ extern "C" {
  *
  * hg_debug_wide_plan: the partition that the persistent 256-row shared-block kernel would use for a level of n_blocks
  * blocks of at most max_rows keys and max_seqs sequences, Hkv KV heads, rows_per_seq query rows per sequence and KV
- * head (queries per sequence x query heads per KV head), at most max_parts partial results per row, on slots_per_xcd
- * CUs of each of the 8 XCDs.  Fills out[9] = { stages per column (32 keys each), columns, row groups, workgroups per
+ * head (queries per sequence x query heads per KV head), head dimension D (128 or 64), at most max_parts partial results
+ * per row, on slots_per_xcd CUs of each of the 8 XCDs.  Fills out[9] = { stages per column (32 keys each at D = 128, 64
+ * keys each at D = 64), columns, row groups, workgroups per
  * team, slots, teams per XCD, stages per team, partial results per row, mode } and returns 1, or returns 0 if the level
  * does not fit.  With n_c stages per column, C columns and N = 8 * teams per XCD teams, team t walks the flattened
  * (column, stage) positions
@@ -33,7 +34,7 @@ extern "C" {
  * work item } and returns 1, or 0 on invalid arguments.
  */
 int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts,
-                       int slots_per_xcd, int out[9]);
+                       int slots_per_xcd, int D, int out[9]);
 int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int page_size, int out[4]);
 
 /*

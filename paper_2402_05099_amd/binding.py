@@ -114,7 +114,7 @@ def lib() -> ctypes.CDLL:
         L.hg_kv_append_fp8.restype = ci
         L.hg_kv_append_paged.argtypes = [vp, vp, vp, ctypes.POINTER(hg_paged_kv), vp, ci, ci, ci, ci]
         L.hg_kv_append_paged.restype = ci
-        L.hg_debug_wide_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
+        L.hg_debug_wide_plan.argtypes = [ci] * 8 + [ctypes.POINTER(ci)]
         L.hg_debug_wide_plan.restype = ci
         L.hg_debug_suffix_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
         L.hg_debug_suffix_plan.restype = ci
@@ -458,10 +458,11 @@ def hg_kv_append_paged(ctx: Context, Knew, Vnew, kv: PagedKV, lengths, capacity:
            "hg_kv_append_paged")
 
 
-def hg_debug_wide_plan(n_blocks: int, max_rows: int, max_seqs: int, Hkv: int, rows_per_seq: int, max_parts: int, slots_per_xcd: int):
+def hg_debug_wide_plan(n_blocks: int, max_rows: int, max_seqs: int, Hkv: int, rows_per_seq: int, max_parts: int, slots_per_xcd: int,
+                       D: int = 128):
     """dict of the persistent shared-block kernel's work partition, or None if the level does not fit (host only)."""
     out = (ctypes.c_int * 9)()
-    if not lib().hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, out):
+    if not lib().hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, D, out):
         return None
     return dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts", "mode"), list(out)))
 

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhydragen.so")
-SOURCES = ["api.hip", "prefix.hip", "prefix_wide.hip", "decode.hip", "merge.hip", "kvcache.hip", "decode_mfma.hip", "fused_small.hip", "ceilings.hip"]
+SOURCES = ["api.hip", "prefix.hip", "prefix_wide.hip", "prefix_wide_d64.hip", "decode.hip", "merge.hip", "kvcache.hip", "decode_mfma.hip", "fused_small.hip", "ceilings.hip"]
 
 # packed fp32 VALU forms are switched off for every device compile of this library
 HIPCC_FLAGS = [

@@ -118,11 +118,13 @@ int hip_rc(hipError_t e) { return e == hipSuccess ? HG_OK : HG_ERR_HIP; }
 // which shared-block kernel runs a level, and how many partial results per row it writes
 struct LevelPlan { bool wide; int ns; WidePlan wp; };
 
-// The persistent 256-row kernel (D = 128) runs a level whose blocks have more than 128 query rows; the 128-row
-// kernel runs the rest and every D = 64 level.  (16 blocks of 128 rows x 512 keys x 40 heads alone: 55 us on the
+// The persistent 256-row kernel runs a level whose blocks have more than 128 query rows; the 128-row
+// kernel runs the rest.  (At D = 128, 16 blocks of 128 rows x 512 keys x 40 heads alone: 55 us on the
 // persistent kernel against 63 us; but inside the fused call its workgroups take whole CUs from the suffix kernel, where
 // 128-row workgroups share them: 0.646 against 0.591 ms on the two-level tree.)
-// HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel wherever D = 128.  max_parts bounds the
+// At D = 64 the same rule holds (fused call on 1024 x 40 heads x 16K keys: 0.351 against 0.377 ms; on the two-level
+// tree the automatic choice gives 0.310 ms against 0.321 with 128-row workgroups only and 0.392 with 256-row only).
+// HG_OPT_PREFIX_KERNEL = 1 forces the 128-row kernel, 2 the 256-row kernel.  max_parts bounds the
 // partial results the plan may use.
 // G: query rows per sequence and KV head (queries per sequence x query heads per KV head).
 LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D, int max_parts, int wide_slots = 32) {
@@ -133,8 +135,8 @@ LevelPlan plan_level(const hg_ctx* c, const LevelDev& lv, int Hkv, int G, int D,
     if (lv.max_rows <= 0) return p;
     if (max_parts < 1) max_parts = 1;
     if (max_parts > HG_MAX_PARTS) max_parts = HG_MAX_PARTS;
-    const bool want_wide = D == 128 && c->opt_prefix_kernel != 1 && (c->opt_prefix_kernel == 2 || rows > kPrefixRowsNarrow);
-    if (want_wide && plan_prefix_wide(lv, Hkv, G, max_parts, c->opt_wide_slots > 0 ? c->opt_wide_slots : wide_slots, &p.wp)) {
+    const bool want_wide = c->opt_prefix_kernel != 1 && (c->opt_prefix_kernel == 2 || rows > kPrefixRowsNarrow);
+    if (want_wide && plan_prefix_wide(lv, Hkv, G, D, max_parts, c->opt_wide_slots > 0 ? c->opt_wide_slots : wide_slots, &p.wp)) {
         p.wide = true;
         p.ns = p.wp.nparts;
         return p;
@@ -172,7 +174,7 @@ int run_level(const void* Q, const LevelDev& lv, LevelPlan plan, int B, int nq, 
     a.out = out;
     if (plan.wide) {
         a.wide = plan.wp;
-        return hip_rc(launch_prefix_wide(a, s));
+        return hip_rc(launch_prefix_wide(a, D, s));
     }
     a.mtiles = ceil_div(lv.max_seqs * a.G * nq, kPrefixRowsNarrow);
     a.nsplit = plan.ns;
@@ -1063,14 +1065,14 @@ int hg_read_stage_timings(hg_ctx* c, float* ms, int n_calls) {
 }
 
 int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts, int slots_per_xcd,
-                       int out[9]) {
-    if (!out || n_blocks < 1 || max_rows < 0 || max_seqs < 0 || Hkv < 1 || rows_per_seq < 1) return 0;
+                       int D, int out[9]) {
+    if (!out || n_blocks < 1 || max_rows < 0 || max_seqs < 0 || Hkv < 1 || rows_per_seq < 1 || (D != 64 && D != 128)) return 0;
     hg::LevelDev lv{};
     lv.n_blocks = n_blocks;
     lv.max_rows = max_rows;
     lv.max_seqs = max_seqs;
     hg::WidePlan p{};
-    if (!hg::plan_prefix_wide(lv, Hkv, rows_per_seq, max_parts, slots_per_xcd, &p)) return 0;
+    if (!hg::plan_prefix_wide(lv, Hkv, rows_per_seq, D, max_parts, slots_per_xcd, &p)) return 0;
     out[0] = p.n_c; out[1] = p.ncols; out[2] = p.rowgroups; out[3] = p.T;
     out[4] = p.slots; out[5] = p.tpx; out[6] = p.quota; out[7] = p.nparts; out[8] = p.mode;
     return 1;

@@ -31,9 +31,9 @@ struct OutDev {
     int64_t part_stride_L;
 };
 
-// Work partition of the persistent 256-row shared-block kernel (prefix_wide.hip).
+// Work partition of the persistent 256-row shared-block kernel (prefix_wide_impl.h).
 struct WidePlan {
-    int n_c;        // 32-key stages per column, from the host's bound on rows per block
+    int n_c;        // stages per column (32 keys each at D = 128, 64 at D = 64), from the host's bound on rows per block
     int ncols;      // columns = n_blocks * Hkv * rowgroups
     int rowgroups;  // groups of at most 32 query-row tiles
     int T;          // workgroups per team = query-row tiles per row group
@@ -146,8 +146,9 @@ struct FillArgs {
 
 // ---- launchers (defined next to their kernels) ------------------------------------------------------
 hipError_t launch_prefix_narrow(const PrefixArgs& a, int D, hipStream_t s);
-hipError_t launch_prefix_wide(const PrefixArgs& a, hipStream_t s);   // D = 128 only; a.wide from plan_prefix_wide
-bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int max_parts, int slots_per_xcd, WidePlan* out);
+hipError_t launch_prefix_wide(const PrefixArgs& a, int D, hipStream_t s);   // a.wide from plan_prefix_wide with the same D
+hipError_t launch_prefix_wide_d64(const PrefixArgs& a, hipStream_t s);      // (the D = 64 kernel lives in its own translation unit)
+bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int D, int max_parts, int slots_per_xcd, WidePlan* out);
 hipError_t launch_decode(const DecodeArgs& a, int D, int GT, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int D, hipStream_t s);   // matrix-core per-sequence kernel (8-bit rows: D = 128 only)
 hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, hipStream_t s);

@@ -228,26 +228,30 @@ def make_workload(
 
 
 # The five benchmark configurations (index 1..5), each with its fixed seed.
-def config(idx: int, P: Optional[int] = None, B: Optional[int] = None, L: Optional[int] = None, **variant) -> Workload:
-    """idx in 1..6.  `P` overrides the level-0 prefix length (config 3 sweeps 1024/4096/16384).
+def config(idx: int, P: Optional[int] = None, B: Optional[int] = None, L: Optional[int] = None, D: Optional[int] = None,
+           **variant) -> Workload:
+    """idx in 1..6.  `P` overrides the level-0 prefix length (config 3 sweeps 1024/4096/16384), `D` the head dimension
+    of configs 2..6 (128 in the paper's models; 64 is the variant the kernels also cover).
 
     6 is the shape of the paper's attention microbenchmark (Sec. 4.2: eight query heads, one KV head, head
     dimension 128), swept over batch size `B`, prefix length `P` and suffix length `L` (every sequence has L rows).
     """
     if idx == 1:
         return make_workload("c1_tiny", 1, 4, 4, 4, 64, [(1, P or 128, 4)], 16, 16, **variant)
+    d = D or 128
+    tag = "" if d == 128 else f"_D{d}"
     if idx == 2:
-        return make_workload("c2_codellama13b", 2, 256, 40, 40, 128, [(1, P or 2048, 256)], 1, 256, **variant)
+        return make_workload("c2_codellama13b" + tag, 2, 256, 40, 40, d, [(1, P or 2048, 256)], 1, 256, **variant)
     if idx == 3:
         p = P or 16384
-        return make_workload(f"c3_long_P{p}", 3, 1024, 40, 40, 128, [(1, p, 1024)], 32, 128, **variant)
+        return make_workload(f"c3_long_P{p}" + tag, 3, 1024, 40, 40, d, [(1, p, 1024)], 32, 128, **variant)
     if idx == 4:
-        return make_workload("c4_gqa", 4, 512, 64, 8, 128, [(1, P or 4096, 512)], 1, 512, **variant)
+        return make_workload("c4_gqa" + tag, 4, 512, 64, 8, d, [(1, P or 4096, 512)], 1, 512, **variant)
     if idx == 5:
-        return make_workload("c5_tree", 5, 2048, 40, 40, 128, [(1, P or 1024, 2048), (16, 512, 128)], 64, 64, **variant)
+        return make_workload("c5_tree" + tag, 5, 2048, 40, 40, d, [(1, P or 1024, 2048), (16, 512, 128)], 64, 64, **variant)
     if idx == 6:
         b, p, l = B or 1024, P or 16384, L or 128
-        return make_workload(f"c6_micro_B{b}_P{p}_L{l}", 6, b, 8, 1, 128, [(1, p, b)], l, l, **variant)
+        return make_workload(f"c6_micro_B{b}_P{p}_L{l}" + tag, 6, b, 8, 1, d, [(1, p, b)], l, l, **variant)
     raise ValueError(f"no config {idx}")
 
 

@@ -147,7 +147,7 @@ def test_prefix_attn(idx, splits, kernel):
     say(f"prefix idx={idx} splits={splits} kernel={kernel}")
     w, dw = workload(idx)
     ctx = dev.make_context(dw, parts=8)
-    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)   # 2 is honoured for D = 128 only
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
     if splits:
         ctx.set_option(hb.HG_OPT_PREFIX_SPLITS, splits)
     Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
@@ -157,6 +157,57 @@ def test_prefix_attn(idx, splits, kernel):
         hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, O, L, dw.scale)
         assert intact()
         check(to_np(O), to_np(L), Oref, Lref, f"prefix idx={idx} splits={splits} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["ragged_1000", "exactly_64", "one_past_64", "short_20", "gqa_tiles", "two_queries", "long_3333"])
+@pytest.mark.parametrize("parts", [8, 1])
+def test_prefix_attn_persistent_kernel_d64(case, parts):
+    """The 256-row kernel at head dimension 64 walks stages of 64 keys (two score tiles per stage): ranges that end
+    inside a stage, inside its first tile, exactly at a stage, a single partial stage, several row tiles, several
+    queries per sequence, and with one part only (whole columns per team)."""
+    say(f"persistent D=64 {case} parts={parts}")
+    B, Hq, Hkv, P, nq = {"ragged_1000": (300, 8, 2, 1000, 1), "exactly_64": (150, 4, 4, 64, 1), "one_past_64": (150, 4, 4, 65, 1),
+                         "short_20": (260, 2, 1, 20, 1), "gqa_tiles": (90, 16, 2, 700, 1), "two_queries": (70, 4, 2, 333, 2),
+                         "long_3333": (40, 8, 8, 3333, 1)}[case]
+    w = wl.make_workload(case, 71, B, Hq, Hkv, 64, [(1, P, B)], 0, 0, lengths=np.zeros(B, np.int32) + nq, nq=nq)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=parts)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, 2)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    lv = dw.levels[0]
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"persistent D=64 {case} parts={parts} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
+def test_persistent_kernel_d64_grouped_and_fused():
+    """Unequal blocks with uncovered sequences at D = 64 on the 256-row kernel, alone and inside the fused call (which
+    picks that kernel by itself for blocks of more than 128 query rows)."""
+    say("persistent D=64 grouped + fused")
+    w = wl.make_workload("gaps64", 23, 400, 8, 4, 64, [(3, 150, 120)], 5, 90)
+    lv = w.levels[0]
+    lv.kv_off = np.array([0, 150, 215, 450], np.int32)    # unequal rows: 150, 65, 235
+    lv.seq_off = np.array([0, 180, 330, 360], np.int32)   # unequal sequences: 180, 150, 30; 360..399 uncovered
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=8)
+    Op, Lp = oracle.attention(w, levels=[0], suffix=False)
+    Of, Lf = oracle.attention(w)
+    assert np.isneginf(Lp[380]).all()
+    for kernel in (2, 0):
+        ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, kernel)
+        O, L, intact = outputs(dw)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[0], O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Op, Lp, f"D=64 grouped kernel={kernel}")
+        O2, L2 = dev.hydragen(ctx, dw, torch.float32)
+        torch.cuda.synchronize()
+        check(to_np(O2), to_np(L2), Of, Lf, f"D=64 fused kernel={kernel}")
+    plan = hb.hg_debug_wide_plan(3, 235, 180, 4, 2, 8, 32, 64)
+    assert plan is not None and plan["n_c"] == 4       # 235 keys: four stages of 64
     ctx.close()
 
 
@@ -205,13 +256,14 @@ def test_grouped_level_with_uncovered_sequences_and_unequal_blocks():
     ctx.close()
 
 
+@pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("kernel", [1, 2], ids=["rows128", "rows256"])
-def test_shared_blocks_ignore_rows_that_are_nobodys_keys(kernel):
+def test_shared_blocks_ignore_rows_that_are_nobodys_keys(kernel, D):
     """Blocks truncated by max_rows leave rows in the level's tensors that are no block's keys; here they hold NaN,
     as do the rows around the blocks.  The kernels re-read a window of 32 rows around a short block (the rows just
     below it, the rows past a range that ends before row 32 of the tensor): none of that may reach a result."""
-    say(f"nobody's keys kernel={kernel}")
-    B, Hq, Hkv, D = 300, 4, 2, 128
+    say(f"nobody's keys kernel={kernel} D={D}")
+    B, Hq, Hkv = 300, 4, 2
     max_rows = 20
     first = 7                               # rows before the first block
     stored = [50, 5, 45]                    # rows each block owns in the tensors

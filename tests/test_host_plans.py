@@ -53,13 +53,14 @@ SHAPES = [
 @pytest.mark.parametrize("shape", SHAPES)
 @pytest.mark.parametrize("slots", [1, 3, 4, 12, 20, 32])
 @pytest.mark.parametrize("max_parts", [1, 2, 3, 24, 64])
-def test_wide_plan_covers_every_stage_once(shape, slots, max_parts):
+@pytest.mark.parametrize("D", [128, 64])
+def test_wide_plan_covers_every_stage_once(shape, slots, max_parts, D):
     n_blocks, max_rows, max_seqs, Hkv, rps = shape
-    plan = hb.hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rps, max_parts, slots)
+    plan = hb.hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rps, max_parts, slots, D)
     assert plan is not None, "one part per row always fits"
     rows = max_seqs * rps
     mtiles = -(-rows // 256)
-    assert plan["n_c"] == -(-max_rows // 32)
+    assert plan["n_c"] == -(-max_rows // (32 if D == 128 else 64))      # a stage is 8 KiB of K at either head dimension
     assert plan["rowgroups"] * plan["T"] >= mtiles and (plan["rowgroups"] - 1) * plan["T"] < mtiles
     assert plan["T"] <= plan["slots"] == slots and plan["tpx"] == slots // plan["T"] >= 1
     assert plan["ncols"] == n_blocks * Hkv * plan["rowgroups"]
@@ -100,6 +101,7 @@ def test_wide_plan_rejects_what_it_cannot_run():
     assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 0, 32) is None     # no room for a result
     assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 4, 33) is None     # more CUs per XCD than there are
     assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 4, 0) is None
+    assert hb.hg_debug_wide_plan(1, 100, 100, 1, 1, 4, 32, 96) is None  # head dimensions other than 64 and 128
 
 
 @pytest.mark.parametrize("B,nq,Hq,Hkv,D,max_len,ps", [
