@@ -74,6 +74,16 @@ def test_full_config3_prefix_sweep():
         torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("idx,P", [(3, 4096), (4, 0), (5, 0)])
+def test_full_config_head_dim_64(idx, P):
+    """The head-dimension-64 variant of the long-context, grouped-head and tree configurations (the persistent
+    shared-block kernel walks 64-key stages there), every row."""
+    say(f"full config {idx} at D=64")
+    w = wl.config(idx, P=P or None, D=64)
+    run_and_check(w, dev.to_device(w), f"config{idx} D=64")
+    torch.cuda.empty_cache()
+
+
 def test_full_config5_tree():
     say("full config 5")
     w = wl.config(5)
