@@ -665,25 +665,45 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     const int G = Hq / Hkv;
     const bool has_suffix = Ks != nullptr && max_len > 0;
 
-    // One launch for everything when the call is small (packed bf16 suffix rows only): a workgroup of four wavefronts
-    // per 32-row tile walks every shared block and the tile's suffixes and merges in LDS (fused_small.hip).  A
-    // wavefront's chain of stages bounds the time: about a quarter of (shared keys + suffix keys of the tile's
-    // sequences) / 32 stages of roughly a microsecond, against three launches, two event edges and a round trip of the
-    // partial results through HBM for the separate kernels (about 45 us when there is nothing else to wait for).
+    // One launch for everything when that is the faster way (packed bf16 suffix rows only): a workgroup of four
+    // wavefronts per 32-row tile walks every shared block and the tile's suffixes and merges in LDS (fused_small.hip),
+    // against three launches, two event edges and a round trip of the partial results through HBM for the separate
+    // kernels.  Both durations are estimated, in microseconds, from fits to measurements on the shape of Sec. 4.2
+    // (eight query heads per KV head, B = 64 .. 2048, 256 .. 16384 shared keys, 128 and 512 suffix rows):
+    //   single launch: 9 + c x (stages of a tile / 4 wavefronts) x rounds of 256 workgroups, c = 1.24 us per 32-key
+    //                  stage while at most half the CUs are busy, 1.6 when the chip is full; never faster than the
+    //                  suffix rows stream in (5.5 TB/s);
+    //   separate:      24 for the launches and the merge + suffix rows at 5 TB/s + shared blocks at 1.1 PFLOP/s, 8 more
+    //                  once a block is long enough to be split.
+    // The host knows only an upper bound of the suffix lengths: the single launch is priced at that bound, the separate
+    // kernels at a mean of 0.75 of it.  The single launch is taken when its estimate is at most 130 us (beyond that the
+    // fit is optimistic: tiles of many short suffixes, 32 per tile with one query row per KV head, pay per segment) and
+    // below the other estimate, by a tenth once it exceeds 40 us.  With ragged lengths this errs towards the separate
+    // kernels (measured on the full-size configurations, single launch against separate kernels: 0.241 / 0.150 ms,
+    // 0.415 / 0.330, 0.578 / 0.370, 0.305 / 0.180, 0.712 / 0.577: there the separate kernels must be, and are, chosen).
     if (!pg.table && !fmt.fp8 && c->opt_fused_kernel != 1 && !c->opt_timing) {
         const int rps = nq * G;
         long long shared_keys = 0;
+        double flops = 0.0;
         bool any = has_suffix;
         for (int i = 0; i < n_levels; ++i) {
             const long long seqs = levels[i].kv_off ? levels[i].max_seqs : B;
-            if (levels[i].max_rows > 0 && seqs > 0) { shared_keys += levels[i].max_rows; any = true; }
+            if (levels[i].max_rows > 0 && seqs > 0) {
+                shared_keys += levels[i].max_rows;
+                flops += 4.0 * levels[i].n_blocks * (double)levels[i].max_rows * seqs * nq * Hq * D;
+                any = true;
+            }
         }
         const int seqs_per_tile = rps >= 32 ? 1 : (32 + rps - 1) / rps + (32 % rps ? 1 : 0);
         const long long stages = (shared_keys + 31) / 32 + (has_suffix ? (long long)seqs_per_tile * ((max_len + 31) / 32) : 0);
         const long long tiles = ((long long)B * rps + 31) / 32;
-        const double waves_rounds = (double)(tiles * Hkv) / 256.0;     // workgroups per CU
-        const double est_us = 6.0 + (double)((stages + 3) / 4) * 1.2 * (waves_rounds > 1.0 ? waves_rounds : 1.0);
-        const bool small = est_us <= 40.0;
+        const double wgs = (double)(tiles * Hkv);
+        const double rounds = wgs > 256.0 ? wgs / 256.0 : 1.0;
+        const double suffix_us = has_suffix ? 4.0 * B * (double)max_len * Hkv * D / 5.0e6 : 0.0;      // at 5 TB/s
+        const double chain_us = 9.0 + (wgs <= 128.0 ? 1.24 : 1.6) * (double)((stages + 3) / 4) * rounds;
+        const double est_single = std::max(chain_us, suffix_us * (5.0 / 5.5) + 4.0);
+        const double est_separate = 24.0 + 0.75 * suffix_us + (shared_keys >= 1024 ? 8.0 : 0.0) + flops / 1.1e9;
+        const bool small = est_single <= 130.0 && est_single <= (est_single <= 40.0 ? 1.0 : 0.9) * est_separate;
         if (any && tiles * Hkv < (1LL << 31) && (c->opt_fused_kernel == 2 || small)) {
             SmallArgs sa{};
             sa.Q = static_cast<const uint16_t*>(Q);
