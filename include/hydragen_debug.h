@@ -49,9 +49,15 @@ int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int
  * real-time ticks } of its loop (cycles / ticks x 100 MHz = the clock the chip ran at).  sink: DEVICE float[1].
  *
  * hg_debug_stream_read: every CU reads `bytes` bytes at src (DEVICE, 16-byte aligned) once, with 16-byte loads.
+ *
+ * hg_debug_xcd_of_workgroups: launches n_workgroups (1..4096) workgroups shaped like the persistent shared-block
+ * kernel's (512 threads, all of a CU's LDS); workgroup i writes the id of the XCD it runs on to out[i] (DEVICE
+ * int32[n_workgroups]).  The shared-block kernels assume out[i] == i % 8 when they put the workgroups that share K/V rows
+ * on one XCD (Sec. 3.2's batching is the same either way: only L2 hits depend on it).
  */
 int hg_debug_mfma_loop(hg_ctx* ctx, int random_operands, int iters, unsigned long long* clocks, float* sink);
 int hg_debug_stream_read(hg_ctx* ctx, const void* src, size_t bytes, float* sink);
+int hg_debug_xcd_of_workgroups(hg_ctx* ctx, int n_workgroups, int* out);
 
 #ifdef __cplusplus
 }

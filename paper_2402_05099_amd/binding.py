@@ -36,7 +36,7 @@ EXPORTS = (
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
     "hg_debug_wide_plan", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
-    "hg_hydragen_attn_static", "hg_debug_mfma_loop", "hg_debug_stream_read",
+    "hg_hydragen_attn_static", "hg_debug_mfma_loop", "hg_debug_stream_read", "hg_debug_xcd_of_workgroups",
 )
 
 
@@ -122,6 +122,8 @@ def lib() -> ctypes.CDLL:
         L.hg_debug_mfma_loop.restype = ci
         L.hg_debug_stream_read.argtypes = [vp, vp, cs, vp]
         L.hg_debug_stream_read.restype = ci
+        L.hg_debug_xcd_of_workgroups.argtypes = [vp, ci, vp]
+        L.hg_debug_xcd_of_workgroups.restype = ci
         L.hg_read_stage_timings.argtypes = [vp, ctypes.POINTER(cf), ci]
         L.hg_read_stage_timings.restype = ci
         L.hg_strerror.argtypes = [ci]
@@ -487,3 +489,9 @@ def hg_debug_stream_read(ctx: Context, src: torch.Tensor, sink: torch.Tensor) ->
     if not src.is_cuda or not src.is_contiguous():
         raise TypeError("src: need a contiguous device tensor")
     _check(lib().hg_debug_stream_read(ctx.h, _p(src), src.numel() * src.element_size(), _p(sink)), "hg_debug_stream_read")
+
+
+def hg_debug_xcd_of_workgroups(ctx: Context, out: torch.Tensor) -> None:
+    """Enqueue out.numel() workgroups shaped like the persistent kernel's; workgroup i writes its XCD to out[i] (int32)."""
+    _want(out, torch.int32, (out.numel(),), "out")
+    _check(lib().hg_debug_xcd_of_workgroups(ctx.h, out.numel(), _p(out)), "hg_debug_xcd_of_workgroups")

@@ -1119,6 +1119,12 @@ int hg_debug_stream_read(hg_ctx* c, const void* src, size_t bytes, float* sink) 
     return hip_rc(hg::launch_stream_read(src, bytes, sink, c->stream));
 }
 
+int hg_debug_xcd_of_workgroups(hg_ctx* c, int n_workgroups, int* out) {
+    if (!c || !out || n_workgroups < 1 || n_workgroups > 4096) return HG_ERR_INVALID_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return HG_ERR_HIP;
+    return hip_rc(hg::launch_xcd_probe(n_workgroups, out, c->stream));
+}
+
 const char* hg_strerror(int code) {
     switch (code) {
         case HG_OK: return "ok";

@@ -93,6 +93,34 @@ hipError_t launch_mfma_loop(int iters, int random_operands, unsigned long long* 
     return hipGetLastError();
 }
 
+// Which XCD a workgroup runs on: the XCC_ID field (bits 3:0) of the hardware register of that name.  The shared-block
+// kernels take workgroup id & 7 for it (workgroups are handed to the XCDs round-robin) when they place the workgroups
+// that share K/V rows on one XCD; only L2 hits depend on that, no result does.  Launched like the persistent kernel:
+// 512 threads and all of a CU's LDS per workgroup.
+__global__ __launch_bounds__(512) void xcd_probe_kernel(int* out) {
+    extern __shared__ unsigned char probe_smem[];
+    if (threadIdx.x == 0) {
+        probe_smem[0] = 1;
+        const unsigned id = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);     // hwreg(HW_REG_XCC_ID, 0, 4)
+        out[blockIdx.x] = (int)(id & 15u) + (probe_smem[0] - 1);
+    }
+}
+
+hipError_t launch_xcd_probe(int n_workgroups, int* out, hipStream_t s) {
+    constexpr int kLds = 160 * 1024;
+    static bool attr_set[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&xcd_probe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+    }
+    xcd_probe_kernel<<<n_workgroups, 512, kLds, s>>>(out);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s) {
     stream_read_kernel<<<256 * 8, 256, 0, s>>>(static_cast<const uintv4*>(src), bytes / 16, sink);
     return hipGetLastError();

@@ -155,6 +155,7 @@ hipError_t launch_merge(const MergeArgs& a, int D, bool in_bf16, bool out_bf16, 
 hipError_t launch_fused_small(const SmallArgs& a, int D, hipStream_t s);
 hipError_t launch_mfma_loop(int iters, int random_operands, unsigned long long* clocks, float* sink, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
+hipError_t launch_xcd_probe(int n_workgroups, int* out, hipStream_t s);
 hipError_t launch_fill_empty(const FillArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t s);
 

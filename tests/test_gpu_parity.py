@@ -606,3 +606,17 @@ def test_fused_call_at_every_workspace_size(idx):
         dev.hydragen(small, dw, torch.float32)
     assert e.value.code == hb.HG_ERR_WORKSPACE
     small.close()
+
+
+def test_workgroups_go_round_robin_over_the_xcds():
+    """The shared-block kernels place the workgroups that share K/V rows on one XCD by taking workgroup id % 8 for the
+    XCD: the hardware's own id register says the same, for a launch shaped like the persistent kernel's."""
+    say("xcd map")
+    ctx = hb.Context(0, 0)
+    for n in (256, 160, 2048):
+        out = torch.full((n,), -1, dtype=torch.int32, device="cuda:0")
+        hb.hg_debug_xcd_of_workgroups(ctx, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.array_equal(got, np.arange(n) % 8), (n, got[:32])
+    ctx.close()
