@@ -52,8 +52,9 @@ int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int
  *
  * hg_debug_xcd_of_workgroups: launches n_workgroups (1..4096) workgroups shaped like the persistent shared-block
  * kernel's (512 threads, all of a CU's LDS); workgroup i writes the id of the XCD it runs on to out[i] (DEVICE
- * int32[n_workgroups]).  The shared-block kernels assume out[i] == i % 8 when they put the workgroups that share K/V rows
- * on one XCD (Sec. 3.2's batching is the same either way: only L2 hits depend on it).
+ * int32[n_workgroups]).  The shared-block kernels assume that out[i] == out[j] exactly when i % 8 == j % 8 (the
+ * XCDs take workgroups round-robin, starting wherever the launch before stopped) when they put the workgroups that share
+ * K/V rows on one XCD (Sec. 3.2's batching is the same either way: only L2 hits depend on it).
  */
 int hg_debug_mfma_loop(hg_ctx* ctx, int random_operands, int iters, unsigned long long* clocks, float* sink);
 int hg_debug_stream_read(hg_ctx* ctx, const void* src, size_t bytes, float* sink);

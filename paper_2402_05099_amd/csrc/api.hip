@@ -497,17 +497,8 @@ int hg_prefix_attn_grouped(hg_ctx* c, const void* Q, const hg_level* level, int 
     if (lv.max_rows == 0 || lv.max_seqs == 0) return fill_empty(O, o_dtype, LSE, rows, D, s);
     if (!plan.wide && (int64_t)lv.n_blocks * ns * Hkv * ceil_div(lv.max_seqs * nq * (Hq / Hkv), kPrefixRowsNarrow) >= (1LL << 28))
         return HG_ERR_UNSUPPORTED;      // (checked before anything is enqueued)
-    if (ns == 1) {
-        if (lv.seq_off) {
-            rc = fill_empty(O, o_dtype, LSE, rows, D, s);
-            if (rc) return rc;
-        }
-        return run_level(Q, lv, plan, B, nq, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
-    }
-    if (lv.seq_off) {
-        rc = fill_empty(nullptr, HG_F32, parts.l(0), rows * ns, D, s);
-        if (rc) return rc;
-    }
+    // (sequences that no block covers are given their empty result by the level's kernel itself)
+    if (ns == 1) return run_level(Q, lv, plan, B, nq, Hq, Hkv, D, scale, direct_out(O, o_dtype, LSE), s);
     rc = run_level(Q, lv, plan, B, nq, Hq, Hkv, D, scale, parts_out(parts, 0), s);
     if (rc) return rc;
     return run_merge(ns, parts, 0, D, O, o_dtype, LSE, s);
@@ -794,15 +785,7 @@ static int fused_impl(hg_ctx* c, const void* Q, int n_levels, const hg_level* le
     hipStream_t s = c->stream;
     if (np == 0) return fill_empty(O_out, o_dtype, LSE_out, rows, D, s);
 
-    // grouped levels may leave sequences uncovered: their partial LSE must read -inf
-    int first = 0;
-    for (int i = 0; i < nlev; ++i) {
-        if (lv[i].seq_off) {
-            rc = fill_empty(nullptr, HG_F32, parts.l(first), rows * ns[i], D, s);
-            if (rc) return rc;
-        }
-        first += ns[i];
-    }
+    // (grouped levels may leave sequences uncovered: the level's kernel marks their partial results empty)
 
     // Two streams unless asked for one.  In automatic mode a call whose levels all run in the persistent kernel on
     // the whole chip stays on one stream (there is no CU left for the suffix kernel to run beside it), and so does a

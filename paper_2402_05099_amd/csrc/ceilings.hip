@@ -93,9 +93,10 @@ hipError_t launch_mfma_loop(int iters, int random_operands, unsigned long long* 
     return hipGetLastError();
 }
 
-// Which XCD a workgroup runs on: the XCC_ID field (bits 3:0) of the hardware register of that name.  The shared-block
-// kernels take workgroup id & 7 for it (workgroups are handed to the XCDs round-robin) when they place the workgroups
-// that share K/V rows on one XCD; only L2 hits depend on that, no result does.  Launched like the persistent kernel:
+// Which XCD a workgroup runs on: the XCC_ID field (bits 3:0) of the hardware register of that name.  Workgroups are
+// handed to the XCDs round-robin, starting wherever the launch before stopped: two workgroups of a launch share an XCD
+// exactly when their ids are equal modulo 8.  The shared-block kernels rely on that when they give the workgroups that
+// share K/V rows ids that are equal modulo 8; only L2 hits depend on it, no result does.  Launched like the persistent kernel:
 // 512 threads and all of a CU's LDS per workgroup.
 __global__ __launch_bounds__(512) void xcd_probe_kernel(int* out) {
     extern __shared__ unsigned char probe_smem[];

@@ -48,9 +48,11 @@ __global__ __launch_bounds__(256, 2) void prefix_kernel(PrefixArgs a) {
     __shared__ __attribute__((aligned(1024))) unsigned char sV0[TILEB];
     __shared__ __attribute__((aligned(1024))) unsigned char sV1[TILEB];
 
+    mark_uncovered(a, D, a.nsplit, blockIdx.x, gridDim.x);
+
     // ---- which tile -------------------------------------------------------------------------------
     const int pid = blockIdx.x;
-    const int L = (pid & 7) * a.per_xcd + (pid >> 3);  // consecutive logical tiles stay on one XCD (ids round-robin over 8 XCDs)
+    const int L = (pid & 7) * a.per_xcd + (pid >> 3);  // consecutive logical tiles stay on one XCD (ids that are equal modulo 8 share an XCD)
     if (L >= a.total_tiles) return;
     int t = L;
     const int mt = t % a.mtiles; t /= a.mtiles;

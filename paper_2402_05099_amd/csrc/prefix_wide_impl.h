@@ -151,10 +151,11 @@ struct WidePiece {
 
 __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
     HG_T(0);
+    mark_uncovered(a, D, a.wide.nparts, blockIdx.x, gridDim.x);
     unsigned char* const smem = wide_smem;
     const WidePlan& p = a.wide;
     const int pid = blockIdx.x;
-    const int xcd = pid & 7, cu_slot = pid >> 3;         // workgroup ids go round-robin over the 8 XCDs
+    const int xcd = pid & 7, cu_slot = pid >> 3;         // workgroups whose ids are equal modulo 8 run on one XCD (which one varies by launch)
     const int team_local = cu_slot / p.T, member = cu_slot % p.T;
     if (team_local >= p.tpx) return;
     const int team = xcd * p.tpx + team_local;
