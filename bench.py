@@ -212,6 +212,27 @@ def measure_config(w, args, hb, dev, torch, steps, warmup):
     return out
 
 
+def device_info(torch):
+    """the GPU the figures were taken on: name, CU count, maximum clock, memory, and the board's power cap if the
+    sensor is readable"""
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "max_clock_MHz": getattr(p, "clock_rate", 0) / 1e3,
+            "memory_GiB": round(p.total_memory / 2 ** 30, 1), "power_cap_W": None}
+    try:
+        caps = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+        if caps:
+            info["power_cap_W"] = int(open(caps[0]).read()) / 1e6
+        if not info["max_clock_MHz"]:      # the driver's table of shader clock levels: the highest one
+            for f in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+                mhz = [int(m) for m in re.findall(r"(\d+)\s*[Mm][Hh]z", open(f).read())]
+                if mhz:
+                    info["max_clock_MHz"] = float(max(mhz))
+                    break
+    except (OSError, ValueError):
+        pass
+    return info
+
+
 def measure_ceilings(hb, torch, ctx):
     """what this chip sustains: the matrix instruction alone (constant / random operands) and a streaming read"""
     clocks = torch.zeros(2, dtype=torch.int64, device="cuda:0")
@@ -369,8 +390,8 @@ def wide_timeline(args, hb, dev, wl, torch):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload index 1..6 (default: the headline config 3; 6 = the paper's microbenchmark shape)")
     ap.add_argument("--batch", type=int, default=0, help="config 6: batch size")
     ap.add_argument("--suffix-len", type=int, default=0, help="config 6: suffix length of every sequence")
@@ -669,6 +690,7 @@ def main() -> int:
         "parity": parity,
         "ceilings": ceilings,
         "configs": configs,
+        "device": device_info(torch),
     }
     print(json.dumps(out))
     if parity is not None and not parity["ok"]:
