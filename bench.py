@@ -376,6 +376,16 @@ def wide_timeline(args, hb, dev, wl, torch):
             print(f"  piece {p}: {int(ok.sum())} workgroups; entry at {(a_ - t0).mean() / 100:.1f}; wait + first scores {(b_ - a_).mean() / 100:.2f} "
                   f"(max {(b_ - a_).max() / 100:.2f}); steps {(c_ - b_).mean() / 100:.2f} (max {(c_ - b_).max() / 100:.2f}) = {cyc.mean():.0f} cycles "
                   f"at {cyc.mean() / ((c_ - b_).mean() * 10):.2f} GHz, {nst.mean():.1f} stages, {cyc.sum() / nst.sum():.0f} cycles per stage; next Q request + result stores {(d_ - c_).mean() / 100:.2f} (max {(d_ - c_).max() / 100:.2f})")
+        # the XCDs one by one (workgroup id % 8; which physical XCD that is varies by launch): the shader clock each ran
+        # piece 0 at, its cycles per stage, and when its workgroups left
+        ok0 = t[:, 3] > t[:, 2]
+        if ok0.all():
+            xcd = np.arange(t.shape[0]) & 7
+            clk = t[:, 16] / ((t[:, 3] - t[:, 2]) * 10.0)
+            cps = t[:, 16] / np.maximum(t[:, 13], 1)
+            print("  by XCD (workgroup id % 8): clock GHz " + " ".join(f"{clk[xcd == x].mean():.3f}" for x in range(8))
+                  + "; cycles per stage " + " ".join(f"{cps[xcd == x].mean():.0f}" for x in range(8))
+                  + "; workgroups leave at " + " ".join(f"{(t[xcd == x, 15] - t0).mean() / 100:.1f}" for x in range(8)))
         ok = t[:, 22] > t[:, 19]
         if ok.any():
             x = t[ok]
