@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 CSRC = os.path.join(ROOT, "paper_2402_05099_amd", "csrc")
 # the source files each kernel's counters depend on (a stored counter reading is only quoted while they are unchanged)
 KERNEL_SOURCES = {
-    "prefix_level": ["prefix_wide.hip", "prefix_wide_step.inc", "prefix.hip", "prefix_common.h", "hg_internal.h"],
+    "prefix_level": ["prefix_wide_impl.h", "prefix_wide.hip", "prefix_wide_step.inc", "prefix.hip", "prefix_common.h", "hg_internal.h"],
     "suffix": ["decode.hip", "decode_mfma.hip", "hg_internal.h"],
 }
 
