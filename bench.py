@@ -363,8 +363,8 @@ def wide_timeline(args, hb, dev, wl, torch):
         print(f"  kernel span {(t[:, 15].max() - t0) / 100:.1f} us; workgroups start between 0 and {(t[:, 0].max() - t0) / 100:.1f} us (mean {(t[:, 0] - t0).mean() / 100:.2f}) "
               f"and leave between {(t[:, 15].min() - t0) / 100:.1f} and {(t[:, 15].max() - t0) / 100:.1f} us; from a workgroup's start to its first piece's entry "
               f"{(t[:, 1] - t[:, 0]).mean() / 100:.2f} (max {(t[:, 1] - t[:, 0]).max() / 100:.2f}): first piece looked up {(t[:, 24] - t[:, 0]).mean() / 100:.2f}, "
-              f"Q requested {(t[:, 25] - t[:, 24]).mean() / 100:.2f}, copy cursor set {(t[:, 26] - t[:, 25]).mean() / 100:.2f}, first stage's copies issued "
-              f"{(t[:, 27] - t[:, 26]).mean() / 100:.2f}, six more stages {(t[:, 1] - t[:, 27]).mean() / 100:.2f}")
+              f"copy cursor set {(t[:, 25] - t[:, 24]).mean() / 100:.2f}, two stages' copies issued {(t[:, 26] - t[:, 25]).mean() / 100:.2f}, Q requested "
+              f"{(t[:, 27] - t[:, 26]).mean() / 100:.2f}, five more stages {(t[:, 1] - t[:, 27]).mean() / 100:.2f}")
         for p in range(3):
             b = 1 + 4 * p
             ok = t[:, b + 3] > t[:, b]

@@ -119,8 +119,8 @@ extern __shared__ __attribute__((aligned(1024))) unsigned char wide_smem[];
 // p, at 1 + 4p + {0 piece entry, 1 first scores done, 2 main loop done, 3 results stored}; slots 16 + p hold the
 // shader-clock cycles of piece p's main loop; slots 19 .. 22 split the boundary between pieces 0 and 1 (next piece
 // looked up, its Q requested, Q landed, barrier passed); slots 13, 14 and 23 hold the number of stages of pieces 0, 1
-// and 2 (a count, not a time); slots 24 .. 27 split the start of the kernel (first piece looked up, its Q requested,
-// copy cursor set, first stage's copies issued).  hg_debug_read_wide_trace copies the table to the host.
+// and 2 (a count, not a time); slots 24 .. 27 split the start of the kernel (first piece looked up, copy cursor set,
+// two stages' copies issued, Q requested).  hg_debug_read_wide_trace copies the table to the host.
 #ifdef HG_TRACE
 constexpr int kTraceSlots = 32;
 __device__ unsigned long long hg_wide_trace[256 * kTraceSlots];
@@ -257,6 +257,25 @@ __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
     } cur{};
     int cf = f0;                     // position of the piece after the cursor's
     int cc = f0 / p.n_c, ck0 = f0 - cc * p.n_c;
+    auto cursor_set = [&](kargs_ptr k, const WidePiece& q) {      // points the cursor at the first stage of piece q (q.nst > 0)
+        // (everything but the lane offsets is uniform; saying so keeps it in scalar registers, where the copy
+        // instructions take their base address from)
+        auto uniform_ptr = [](const uint16_t* ptr) {
+            const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+            return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
+        };
+        cur.Kg = uniform_ptr(k->lv.K + (int64_t)q.kvh * D);
+        cur.Vg = uniform_ptr(k->lv.V + (int64_t)q.kvh * D);
+        cur.ks = __builtin_amdgcn_readfirstlane(q.ks);
+        cur.kwin = __builtin_amdgcn_readfirstlane(q.kwin);
+        cur.t = 0;
+        cur.left = __builtin_amdgcn_readfirstlane((q.nst + NS - 1) & ~(NS - 1));     // the stream pads every piece to whole groups of NS stages
+        const int row = min(srow, q.ke - 1 - q.kwin);    // binds only when the range ends before row KT of the tensor
+        cur.voffK = (unsigned)row * rstride_b + (unsigned)((sch ^ kswz(srow)) * 16);
+        cur.voffV = (unsigned)row * rstride_b + (unsigned)((sch ^ vswz(srow)) * 16);
+        cur.valid = 1;
+    };
     auto cursor_next_piece = [&](kargs_ptr k) {          // moves the cursor to the next piece that has stages, if there is one
         while (cf < f1) {
             WidePiece q;
@@ -265,23 +284,7 @@ __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
             ++cc;
             ck0 = 0;
             if (q.nst > 0) {
-                // (everything but the lane offsets is uniform; saying so keeps it in scalar registers, where the copy
-                // instructions take their base address from)
-                auto uniform_ptr = [](const uint16_t* ptr) {
-                    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
-                    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-                    return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
-                };
-                cur.Kg = uniform_ptr(k->lv.K + (int64_t)q.kvh * D);
-                cur.Vg = uniform_ptr(k->lv.V + (int64_t)q.kvh * D);
-                cur.ks = __builtin_amdgcn_readfirstlane(q.ks);
-                cur.kwin = __builtin_amdgcn_readfirstlane(q.kwin);
-                cur.t = 0;
-                cur.left = __builtin_amdgcn_readfirstlane((q.nst + NS - 1) & ~(NS - 1));     // the stream pads every piece to whole groups of NS stages
-                const int row = min(srow, q.ke - 1 - q.kwin);    // binds only when the range ends before row 32 of the tensor
-                cur.voffK = (unsigned)row * rstride_b + (unsigned)((sch ^ kswz(srow)) * 16);
-                cur.voffV = (unsigned)row * rstride_b + (unsigned)((sch ^ vswz(srow)) * 16);
-                cur.valid = 1;
+                cursor_set(k, q);
                 return;
             }
         }
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
     constexpr int kStoresPerPiece = D / 8 + 1;     // result stores of a wavefront whose 32 rows all exist: 16 of O, 1 of LSE
     enum { kQFirst = 0, kQAfterStores = 1, kQDrain = 2 };
     auto wait_q = [&](int kind) {
-        constexpr int kFirst = (NS - 3) * 2;       // kernel start: Q, then NS-1 stages; stages 2 .. NS-2 may stay in flight
+        constexpr int kFirst = (NS - 3) * 2;       // kernel start: two stages, Q, then NS-3 stages more, which may stay in flight
         if (kind == kQFirst) __builtin_amdgcn_s_waitcnt(0x0F70 | (kFirst & 15) | ((kFirst >> 4) << 14));
         else if (kind == kQAfterStores) __builtin_amdgcn_s_waitcnt(0x0F70 | (kStoresPerPiece & 15) | ((kStoresPerPiece >> 4) << 14));
         else __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -520,17 +523,22 @@ __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
         const kargs_ptr k = kargs();       // one look at the arguments for everything up to the first copies
         if (!next_piece(k)) return;
         HG_T(24);
-        load_q(k, row_ctx(k, pc));
+        // the copy cursor starts at the piece the compute side has just found (the pieces before it have no stages); its
+        // first two stages are requested before Q, which the first products need together with them
+        cf = pf;
+        cc = pcol;
+        ck0 = pk0;
+        cursor_set(k, pc);
         HG_T(25);
-        cursor_next_piece(k);               // finds at least the piece next_piece() found
+        issue_stage(0);
+        issue_stage(1);
         HG_T(26);
+        load_q(k, row_ctx(k, pc));
+        HG_T(27);
     }
     int qkind = kQFirst;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
-        issue_stage(s);
-        if (s == 0) HG_T(27);
-    }
+    for (int s = 2; s < NS - 1; ++s) issue_stage(s);
     int piece_no = 0;
 
     for (;;) {
