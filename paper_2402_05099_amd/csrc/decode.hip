@@ -42,9 +42,28 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char*
 template <int D, int GT, bool FP8>
 constexpr int epl_of() { return (FP8 && D == 128 && GT <= 2) ? 16 : 8; }
 
+// bf16 rows are multiplied two elements at a time with v_dot2_f32_bf16 (products of bf16 values are exact in fp32, the
+// sums are taken in fp32): a score is four such instructions on the packed words of K and Q as they come from memory,
+// and the value sums take the rounded weights of two keys against those keys' values of one column.  Set to 0 to fall
+// back to unpacking every element to fp32 first (four times the instructions for the scores, twice for the values).
+#ifndef HG_DECODE_DOT2
+#define HG_DECODE_DOT2 1
+#endif
+typedef __bf16 bf16pair __attribute__((ext_vector_type(2)));
+typedef float f32pair __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_pair_bf16(float lo, float hi) {      // v_cvt_pk_bf16_f32, round to nearest even
+    f32pair f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16pair));
+}
+__device__ __forceinline__ float dot2_bf16(unsigned a, unsigned b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16pair, a), __builtin_bit_cast(bf16pair, b), c, false);
+}
+
 template <int D, int GT, int EPL = 8>
 struct DecodeState {
     float q[GT][EPL];    // query elements of this lane's column slice, pre-multiplied by scale*log2(e)
+    unsigned qp[GT][EPL / 2];   // the same elements as packed bf16 pairs, unscaled (bf16 rows with HG_DECODE_DOT2)
+    float qs;            // scale*log2(e), applied to a score after its sum (same case)
     float m[GT];         // running max (log2 domain)
     float l[GT];         // running sum of 2^(s-m)
     float acc[GT][EPL];  // running sum of 2^(s-m) * v
@@ -130,15 +149,26 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT, EPL>& st, const
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const bool ok = first + u * KPW < n;
-        float k[EPL];
-        unpack8(bt.k[u], k);
+        if constexpr (!FP8 && HG_DECODE_DOT2) {
+            const unsigned kw[4] = {bt.k[u].x, bt.k[u].y, bt.k[u].z, bt.k[u].w};
 #pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float d = st.q[g][0] * k[0];
+            for (int g = 0; g < GT; ++g) {
+                const float d0 = dot2_bf16(kw[2], st.qp[g][2], dot2_bf16(kw[0], st.qp[g][0], 0.f));     // two chains of two
+                const float d1 = dot2_bf16(kw[3], st.qp[g][3], dot2_bf16(kw[1], st.qp[g][1], 0.f));
+                const float d = row_allreduce_sum<LPR>(d0 + d1) * st.qs;
+                s[u][g] = ok ? d : -INFINITY;
+            }
+        } else {
+            float k[EPL];
+            unpack8(bt.k[u], k);
 #pragma unroll
-            for (int j = 1; j < EPL; ++j) d = fmaf(st.q[g][j], k[j], d);
-            d = row_allreduce_sum<LPR>(d);
-            s[u][g] = ok ? d : -INFINITY;
+            for (int g = 0; g < GT; ++g) {
+                float d = st.q[g][0] * k[0];
+#pragma unroll
+                for (int j = 1; j < EPL; ++j) d = fmaf(st.q[g][j], k[j], d);
+                d = row_allreduce_sum<LPR>(d);
+                s[u][g] = ok ? d : -INFINITY;
+            }
         }
     }
 #pragma unroll
@@ -159,12 +189,31 @@ __device__ __forceinline__ void consume_batch(DecodeState<D, GT, EPL>& st, const
         st.l[g] = fmaf(st.l[g], alpha, ps);
 #pragma unroll
         for (int j = 0; j < EPL; ++j) st.acc[g][j] *= alpha;
+        if constexpr (!FP8 && HG_DECODE_DOT2) {
+            static_assert(FP8 || U % 2 == 0, "keys are taken in pairs");
+            // weights of two keys, rounded to bf16 (as the matrix-core kernels round theirs; the row sum above keeps
+            // the unrounded ones), against the two keys' values of one column: v_perm_b32 gathers the column's pair
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float v[EPL];
-            unpack8(bt.v[u], v);
+            for (int u = 0; u < U; u += 2) {
+                const unsigned pp = pack_pair_bf16(p[u], p[u + 1]);
+                const unsigned va[4] = {bt.v[u].x, bt.v[u].y, bt.v[u].z, bt.v[u].w};
+                const unsigned vb[4] = {bt.v[u + 1].x, bt.v[u + 1].y, bt.v[u + 1].z, bt.v[u + 1].w};
 #pragma unroll
-            for (int j = 0; j < EPL; ++j) st.acc[g][j] = fmaf(p[u], v[j], st.acc[g][j]);
+                for (int w = 0; w < 4; ++w) {
+                    const unsigned lo = __builtin_amdgcn_perm(vb[w], va[w], 0x05040100u);   // (va.lo, vb.lo)
+                    const unsigned hi = __builtin_amdgcn_perm(vb[w], va[w], 0x07060302u);   // (va.hi, vb.hi)
+                    st.acc[g][2 * w] = dot2_bf16(lo, pp, st.acc[g][2 * w]);
+                    st.acc[g][2 * w + 1] = dot2_bf16(hi, pp, st.acc[g][2 * w + 1]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float v[EPL];
+                unpack8(bt.v[u], v);
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) st.acc[g][j] = fmaf(p[u], v[j], st.acc[g][j]);
+            }
         }
     }
 }
@@ -315,6 +364,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
             for (int h8 = 0; h8 < EPL / 8; ++h8) {
                 const uint4 qv = *reinterpret_cast<const uint4*>(a.Q + ((int64_t)bq * a.Hq + h0 + g) * D + col + 8 * h8);
                 float* const q = &st.q[g][8 * h8];
+                st.qp[g][4 * h8] = qv.x; st.qp[g][4 * h8 + 1] = qv.y; st.qp[g][4 * h8 + 2] = qv.z; st.qp[g][4 * h8 + 3] = qv.w;
                 q[0] = bf16_lo(qv.x) * qs; q[1] = bf16_hi(qv.x) * qs;
                 q[2] = bf16_lo(qv.y) * qs; q[3] = bf16_hi(qv.y) * qs;
                 q[4] = bf16_lo(qv.z) * qs; q[5] = bf16_hi(qv.z) * qs;
@@ -325,6 +375,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
 #pragma unroll
             for (int j = 0; j < EPL; ++j) st.acc[g][j] = 0.f;
         }
+        st.qs = qs;
     }
 
     // walk the concatenated key list (shared blocks root first, then the suffix), clipped to this chunk
