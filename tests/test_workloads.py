@@ -38,3 +38,14 @@ def test_config_shapes():
     assert np.all(w.lengths == 16) and abs(w.scale - 0.125) < 1e-15
     t = wl.scaled_down(5)
     assert t.levels[1].Gn == 4 and t.kv_rows_of(25) == [(0, 0, 200), (1, 77, 154)]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU: asking for more exits with a message that says so (before anything touches a GPU)."""
+    import subprocess
+    import sys
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
