@@ -26,7 +26,14 @@ extern "C" {
  *                   per piece, numbered t - floor(column * n_c / quota);
  *   mode 1, C <= N: column c = floor(t * C / N) belongs to the teams ceil(c * N / C) .. ceil((c+1) * N / C) - 1; the
  *                   i-th of its n teams walks its stages [floor(i * n_c / n), floor((i+1) * n_c / n)), part i;
- *   mode 1, C > N:  the whole columns floor(t * C / N) .. floor((t+1) * C / N) - 1, part 0.
+ *   mode 1, C > N:  the whole columns floor(t * C / N) .. floor((t+1) * C / N) - 1, part 0;
+ *   mode 2:         [starts[t], starts[t+1]) from hg_debug_wide_ranges: ranges of equal cost, a column boundary inside a
+ *                   range counting as 9 stages (the workgroups store a result and load a Q tile there); the team's
+ *                   first piece is part first_part[t] of its column, its later pieces part 0 of theirs.  out[6] is then
+ *                   the cost bound, not a length.
+ *
+ * hg_debug_wide_ranges: the same arguments; fills starts[257] and first_part[256] for a mode 2 partition and returns the
+ * number of teams N (entries beyond N are not written), or returns 0 if the partition is not of mode 2.
  *
  * hg_debug_suffix_plan: the suffix kernel and chunking chosen with default options for B sequences of at most max_len
  * suffix rows, nq queries each, Hq / Hkv heads of dimension D (page_size > 0: paged cache).  Fills out[4] = { keys per
@@ -35,6 +42,8 @@ extern "C" {
  */
 int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts,
                        int slots_per_xcd, int D, int out[9]);
+int hg_debug_wide_ranges(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts,
+                         int slots_per_xcd, int D, int starts[257], int first_part[256]);
 int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int page_size, int out[4]);
 
 /*

@@ -35,7 +35,7 @@ EXPORTS = (
     "hg_create", "hg_destroy", "hg_set_stream", "hg_set_option", "hg_workspace_bytes", "hg_prefix_attn",
     "hg_prefix_attn_grouped", "hg_suffix_attn", "hg_merge", "hg_hydragen_attn", "hg_naive_attn", "hg_read_stage_timings",
     "hg_strerror", "hg_suffix_attn_paged", "hg_hydragen_attn_paged", "hg_kv_append", "hg_kv_append_paged",
-    "hg_debug_wide_plan", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
+    "hg_debug_wide_plan", "hg_debug_wide_ranges", "hg_debug_suffix_plan", "hg_suffix_attn_fp8", "hg_hydragen_attn_fp8", "hg_kv_append_fp8",
     "hg_hydragen_attn_static", "hg_debug_mfma_loop", "hg_debug_stream_read", "hg_debug_xcd_of_workgroups",
 )
 
@@ -116,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.hg_kv_append_paged.restype = ci
         L.hg_debug_wide_plan.argtypes = [ci] * 8 + [ctypes.POINTER(ci)]
         L.hg_debug_wide_plan.restype = ci
+        L.hg_debug_wide_ranges.argtypes = [ci] * 8 + [ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.hg_debug_wide_ranges.restype = ci
         L.hg_debug_suffix_plan.argtypes = [ci] * 7 + [ctypes.POINTER(ci)]
         L.hg_debug_suffix_plan.restype = ci
         L.hg_debug_mfma_loop.argtypes = [vp, ci, ci, vp, vp]
@@ -466,7 +468,13 @@ def hg_debug_wide_plan(n_blocks: int, max_rows: int, max_seqs: int, Hkv: int, ro
     out = (ctypes.c_int * 9)()
     if not lib().hg_debug_wide_plan(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, D, out):
         return None
-    return dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts", "mode"), list(out)))
+    plan = dict(zip(("n_c", "ncols", "rowgroups", "T", "slots", "tpx", "quota", "nparts", "mode"), list(out)))
+    if plan["mode"] == 2:      # ranges from the planner's table
+        starts, first = (ctypes.c_int * 257)(), (ctypes.c_int * 256)()
+        n = lib().hg_debug_wide_ranges(n_blocks, max_rows, max_seqs, Hkv, rows_per_seq, max_parts, slots_per_xcd, D, starts, first)
+        assert n == 8 * plan["tpx"]
+        plan["starts"], plan["first_part"] = list(starts)[:n + 1], list(first)[:n]
+    return plan
 
 
 def hg_debug_suffix_plan(B: int, nq: int, Hq: int, Hkv: int, D: int, max_len: int, page_size: int = 0):

@@ -1081,6 +1081,21 @@ int hg_debug_wide_plan(int n_blocks, int max_rows, int max_seqs, int Hkv, int ro
     return 1;
 }
 
+int hg_debug_wide_ranges(int n_blocks, int max_rows, int max_seqs, int Hkv, int rows_per_seq, int max_parts, int slots_per_xcd,
+                         int D, int starts[257], int first_part[256]) {
+    if (!starts || !first_part || n_blocks < 1 || max_rows < 0 || max_seqs < 0 || Hkv < 1 || rows_per_seq < 1 || (D != 64 && D != 128)) return 0;
+    hg::LevelDev lv{};
+    lv.n_blocks = n_blocks;
+    lv.max_rows = max_rows;
+    lv.max_seqs = max_seqs;
+    hg::WidePlan p{};
+    if (!hg::plan_prefix_wide(lv, Hkv, rows_per_seq, D, max_parts, slots_per_xcd, &p) || p.mode != 2) return 0;
+    const int nteams = 8 * p.tpx;
+    for (int t = 0; t <= nteams; ++t) starts[t] = p.starts[t];
+    for (int t = 0; t < nteams; ++t) first_part[t] = p.first_part[t];
+    return nteams;
+}
+
 int hg_debug_suffix_plan(int B, int nq, int Hq, int Hkv, int D, int max_len, int page_size, int out[4]) {
     if (!out || B < 1 || nq < 1 || Hkv < 1 || Hq < Hkv || Hq % Hkv != 0 || (D != 64 && D != 128) || max_len < 0 || page_size < 0) return 0;
     hg_ctx c{};   // default options

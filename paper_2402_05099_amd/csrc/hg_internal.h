@@ -31,6 +31,9 @@ struct OutDev {
     int64_t part_stride_L;
 };
 
+constexpr int kWideMaxTeams = 256;        // one team per CU at most
+constexpr int kWideBoundaryCost = 9;      // stages a piece boundary costs a workgroup (measured: 8 us at 0.85 us per stage)
+
 // Work partition of the persistent 256-row shared-block kernel (prefix_wide_impl.h).
 struct WidePlan {
     int n_c;        // stages per column (32 keys each at D = 128, 64 at D = 64), from the host's bound on rows per block
@@ -43,7 +46,11 @@ struct WidePlan {
     int nparts;     // partial results per query row
     int mode;       // how the flattened (column, stage) space is cut into one contiguous range per team:
                     // 0: equal ranges of `quota` stages; 1: ranges that never straddle a column boundary (each column
-                    // cut evenly among its own teams, or whole columns per team when there are more columns than teams)
+                    // cut evenly among its own teams, or whole columns per team when there are more columns than teams);
+                    // 2: ranges of equal cost from the table below (a column boundary inside a range counts as
+                    // kWideBoundaryCost stages: the team's workgroups store a result and load a Q tile there)
+    int starts[kWideMaxTeams + 1];      // mode 2: team t walks [starts[t], starts[t + 1])
+    int first_part[kWideMaxTeams];      // mode 2: part index of team t's first piece (pieces of its column before it)
 };
 
 struct PrefixArgs {

@@ -171,6 +171,10 @@ __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
         f0 = (int)lo;
         f1 = (int)(lo + p.quota < total ? lo + p.quota : total);
         sp0 = team - (int)((unsigned)(f0 / p.n_c * p.n_c) / (unsigned)p.quota);
+    } else if (p.mode == 2) {     // ranges of equal cost, from the planner's table
+        f0 = p.starts[team];
+        f1 = p.starts[team + 1];
+        sp0 = p.first_part[team];
     } else if (p.ncols <= nteams) {   // every column is cut evenly among its own teams
         const int c = team * p.ncols / nteams;
         const int tf = (c * nteams + p.ncols - 1) / p.ncols;
@@ -834,6 +838,68 @@ bool plan_prefix_wide(const LevelDev& lv, int Hkv, int G, int D, int max_parts, 
     if (q >= (1LL << 30)) return false;
     p.quota = (int)q;
     p.nparts = np;
+    // Equal ranges, some with a column boundary inside and some without: the teams with a boundary finish later by what
+    // a second piece costs.  Ranges of equal cost instead (cost = stages + kWideBoundaryCost per boundary inside): the
+    // smallest cost C for which the teams, each taking the longest range that costs at most C, cover the space.
+    if (p.mode == 0 && nteams <= kWideMaxTeams) {
+        const long long nc = p.n_c, kappa = kWideBoundaryCost;
+        auto end_of = [&](long long a, long long C) {      // the largest b <= total with (b - a) + kappa * boundaries inside (a, b) <= C
+            long long best = a + 1;
+            const long long m0 = a / nc * nc;
+            for (long long k = 0; C - kappa * k >= 1; ++k) {
+                const long long mk = k == 0 ? a : m0 + k * nc;            // k boundaries lie inside when b > m_k
+                const long long b = std::min({m0 + (k + 1) * nc, a + C - kappa * k, total});
+                if (b > mk) best = std::max(best, b);
+                if (mk >= total) break;
+            }
+            return std::min(best, total);
+        };
+        auto covers = [&](long long C) {
+            long long a = 0;
+            for (int t = 0; t < nteams && a < total; ++t) a = end_of(a, C);
+            return a >= total;
+        };
+        int with = 0, without = 0;
+        long long cost0 = 0;
+        for (int t = 0; t < nteams; ++t) {
+            const long long lo = (long long)t * q, hi = std::min<long long>(lo + q, total);
+            if (lo >= hi) break;
+            const long long inner = (hi - 1) / nc - lo / nc;
+            (inner ? with : without) += 1;
+            cost0 = std::max(cost0, hi - lo + kappa * inner);
+        }
+        if (with && without) {
+            long long lo = (total + nteams - 1) / nteams, hi = cost0;       // covers(hi) holds: equal ranges cost at most cost0
+            while (lo < hi) {
+                const long long mid = (lo + hi) / 2;
+                if (covers(mid)) hi = mid;
+                else lo = mid + 1;
+            }
+            if (hi < cost0) {
+                WidePlan w = p;
+                long long a = 0;
+                int col = -1, in_col = 0, np2 = 1;
+                for (int t = 0; t <= nteams; ++t) w.starts[t] = (int)total;
+                for (int t = 0; t < nteams && a < total; ++t) {
+                    const long long b = end_of(a, hi);
+                    w.starts[t] = (int)a;
+                    for (long long c = a / nc; c <= (b - 1) / nc; ++c) {       // the pieces of this team, column by column
+                        if ((int)c != col) { col = (int)c; in_col = 0; }
+                        if (c == a / nc) w.first_part[t] = in_col;
+                        ++in_col;
+                        np2 = std::max(np2, in_col);
+                    }
+                    a = b;
+                }
+                if (np2 <= max_parts) {
+                    w.mode = 2;
+                    w.nparts = np2;
+                    w.quota = (int)hi;      // (the cost bound; not a length in this mode)
+                    p = w;
+                }
+            }
+        }
+    }
     *out = p;
     return true;
 }

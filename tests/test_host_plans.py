@@ -18,7 +18,9 @@ def walk(plan):
     pieces = {}
     nteams = 8 * plan["tpx"]
     for team in range(nteams):
-        if plan["mode"] == 0:
+        if plan["mode"] == 2:
+            f0, f1, sp = plan["starts"][team], plan["starts"][team + 1], plan["first_part"][team]
+        elif plan["mode"] == 0:
             f0, f1 = team * quota, (team + 1) * quota
             sp = team - (f0 // n_c * n_c) // quota
         elif ncols <= nteams:
@@ -91,9 +93,24 @@ def test_wide_plan_aligns_short_pieces_to_columns():
             per_team.setdefault(team, []).append(ln)
     assert all(len(v) == 1 for v in per_team.values()) and len(per_team) == 256
     assert max(v[0] for v in per_team.values()) == 11 and min(v[0] for v in per_team.values()) == 9
-    # long columns keep equal ranges (config 3 at 16K keys: 64 teams x 320 stages)
+
+
+def test_wide_plan_gives_ranges_of_equal_cost():
+    """Config 3 at 16K keys (40 columns of 512 stages on 64 teams): equal ranges of 320 stages put a column boundary into
+    every second team's range.  Ranges of equal cost, a boundary counting as nine stages: 325 stages without a boundary,
+    316 with one (321 for a team that ends its column), every (column, stage) still covered once, three parts at most."""
     plan = hb.hg_debug_wide_plan(1, 16384, 1024, 40, 1, 24, 32)
-    assert plan["mode"] == 0 and plan["quota"] == 320
+    assert plan["mode"] == 2 and plan["nparts"] == 3 and plan["quota"] == 325
+    starts = plan["starts"]
+    assert starts[0] == 0 and starts[-1] == 40 * 512 and all(a <= b for a, b in zip(starts, starts[1:]))
+    for t in range(64):
+        f0, f1 = starts[t], starts[t + 1]
+        inner = (f1 - 1) // 512 - f0 // 512
+        assert inner <= 1 and (f1 - f0) + 9 * inner <= 325
+        assert (f1 - f0) + 9 * inner >= 321                      # nobody is short of work either
+    # when every team has a boundary (or none has) the equal ranges stay: config 5's root, config 4
+    assert hb.hg_debug_wide_plan(1, 1024, 2048, 40, 1, 24, 32)["mode"] == 0
+    assert hb.hg_debug_wide_plan(1, 4096, 512, 8, 8, 24, 32)["mode"] == 0
 
 
 def test_wide_plan_rejects_what_it_cannot_run():
