@@ -120,7 +120,7 @@ extern __shared__ __attribute__((aligned(1024))) unsigned char wide_smem[];
 // shader-clock cycles of piece p's main loop; slots 19 .. 22 split the boundary between pieces 0 and 1 (next piece
 // looked up, its Q requested, Q landed, barrier passed); slots 13, 14 and 23 hold the number of stages of pieces 0, 1
 // and 2 (a count, not a time); slots 24 .. 27 split the start of the kernel (first piece looked up, copy cursor set,
-// two stages' copies issued, Q requested).  hg_debug_read_wide_trace copies the table to the host.
+// two stages' copies issued, Q requested); slot 28 holds the id of the XCD the workgroup ran on.  hg_debug_read_wide_trace copies the table to the host.
 #ifdef HG_TRACE
 constexpr int kTraceSlots = 32;
 __device__ unsigned long long hg_wide_trace[256 * kTraceSlots];
@@ -151,6 +151,9 @@ struct WidePiece {
 
 __global__ __launch_bounds__(64 * NW, 1) void HG_WIDE_KERNEL(PrefixArgs a) {
     HG_T(0);
+#ifdef HG_TRACE
+    if (threadIdx.x == 0) hg_wide_trace[blockIdx.x * kTraceSlots + 28] = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;   // XCC_ID
+#endif
     mark_uncovered(a, D, a.wide.nparts, blockIdx.x, gridDim.x);
     unsigned char* const smem = wide_smem;
     const WidePlan& p = a.wide;
