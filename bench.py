@@ -359,7 +359,7 @@ def wide_timeline(args, hb, dev, wl, torch):
         assert L.hg_debug_read_wide_trace(buf.ctypes.data_as(ctypes.c_void_p)) == 0
         t = buf.reshape(256, 32).astype(np.float64)[:8 * plan["slots"]]
         t0 = t[:, 0].min()
-        print(f"level {li}: plan {plan}")
+        print(f"level {li}: plan { {k: v for k, v in plan.items() if k not in ('starts', 'first_part')} }")
         print(f"  kernel span {(t[:, 15].max() - t0) / 100:.1f} us; workgroups start between 0 and {(t[:, 0].max() - t0) / 100:.1f} us (mean {(t[:, 0] - t0).mean() / 100:.2f}) "
               f"and leave between {(t[:, 15].min() - t0) / 100:.1f} and {(t[:, 15].max() - t0) / 100:.1f} us; from a workgroup's start to its first piece's entry "
               f"{(t[:, 1] - t[:, 0]).mean() / 100:.2f} (max {(t[:, 1] - t[:, 0]).max() / 100:.2f}): first piece looked up {(t[:, 24] - t[:, 0]).mean() / 100:.2f}, "
