@@ -334,6 +334,32 @@ def test_persistent_kernel_partitions(name, B, Hq, Hkv, P, parts):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,n_blocks,P,B,Hq,Hkv,D,slots,nparts", [
+    ("five_columns_eight_teams", 1, 2500, 300, 5, 5, 128, 2, 3),     # ranges of 54 stages without a column boundary, 45 with one
+    ("five_columns_eight_teams_d64", 1, 2500, 300, 5, 5, 64, 2, 2),
+    ("two_blocks_three_tiles", 2, 1300, 145, 6, 3, 128, 3, 2),       # 290 rows per block and KV head: teams of three workgroups
+])
+def test_persistent_kernel_ranges_of_equal_cost(name, n_blocks, P, B, Hq, Hkv, D, slots, nparts):
+    """Where equal ranges would give some teams a column boundary and others none, the planner hands out ranges of equal
+    cost from a table (a boundary counts as nine stages): every key is still multiplied exactly once."""
+    say(f"equal-cost ranges {name}")
+    G = Hq // Hkv
+    plan = hb.hg_debug_wide_plan(n_blocks, P, B, Hkv, G, 8, slots, D)
+    assert plan["mode"] == 2 and plan["nparts"] == nparts, plan
+    w = wl.make_workload(name, 79, B * n_blocks, Hq, Hkv, D, [(n_blocks, P, B)], 0, 0)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=8)
+    ctx.set_option(hb.HG_OPT_PREFIX_KERNEL, 2)
+    ctx.set_option(hb.HG_OPT_WIDE_SLOTS, slots)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    for dtype in (torch.float32, torch.bfloat16):
+        O, L, intact = outputs(dw, dtype)
+        hb.hg_prefix_attn_grouped(ctx, dw.Q, dw.levels[0], O, L, dw.scale)
+        assert intact()
+        check(to_np(O), to_np(L), Oref, Lref, f"equal-cost ranges {name} {dtype}", out_bf16=dtype == torch.bfloat16)
+    ctx.close()
+
+
 VARIANTS = [dict(), dict(q_gain=4.0), dict(plant="suffix"), dict(plant="prefix")]
 
 
