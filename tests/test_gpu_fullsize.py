@@ -84,6 +84,27 @@ def test_full_config_head_dim_64(idx, P):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("P", [4096, 16384])
+def test_full_config3_shared_block_alone(P):
+    """The shared-block call by itself on the whole chip, as bench.py's serialised pass times it (the partition differs
+    from the one inside the fused call: 64 teams with ranges of equal cost), every row against the oracle."""
+    say(f"full config 3, shared block alone, P={P}")
+    w = wl.config(3, P=P)
+    dw = dev.to_device(w)
+    ctx = dev.make_context(dw, parts=24)
+    Oref, Lref = oracle.attention(w, levels=[0], suffix=False)
+    O = torch.full(dw.lead + (dw.D,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    L = torch.full(dw.lead, float("nan"), dtype=torch.float32, device="cuda:0")
+    lv = dw.levels[0]
+    hb.hg_prefix_attn(ctx, dw.Q, lv.K, lv.V, O, L, dw.scale)
+    torch.cuda.synchronize()
+    st = check(to_np(O), to_np(L), Oref, Lref, f"config3 P={P} shared block", out_bf16=True)
+    say(f"   config3 P={P} shared block alone: all {w.B * w.Hq} rows: max|dO|={st['max_abs_dO']:.3e} (max|O|={st['max_abs_O']:.3e}) "
+        f"rel-L2={st['rel_l2']:.3e} max|dLSE|={st['max_abs_dLSE']:.3e}")
+    ctx.close()
+    torch.cuda.empty_cache()
+
+
 def test_full_config5_tree():
     say("full config 5")
     w = wl.config(5)
