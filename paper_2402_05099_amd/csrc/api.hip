@@ -324,18 +324,18 @@ int pick_wide_slots(double flops, double bytes, int T) {
         // (when teams are so wide that no smaller count does, the general model below decides)
         for (int s = 4; s < 32; s += 4) {
             const int eff = s / T * T;
-            if (eff >= 4 && flops / (full_rate * rate_at(eff)) <= 0.5 * ts) return s;
+            if (eff >= 4 && flops / (full_rate * rate_at(eff)) <= 0.5 * ts) return eff;
         }
     }
     int best = 32;
     double best_t = 1e30;
     for (int s = 32; s >= 4; s -= 4) {
-        const int eff = s / T * T;                 // CUs per XCD that hold whole teams; the others are released at once
+        const int eff = s / T * T;                 // CUs per XCD that hold whole teams (no workgroup is launched on the others)
         if (eff < 4) break;
         const double tp = flops / (full_rate * rate_at(eff));
         const double conc = 0.7 * bw * (256 - 8 * eff) / 256.0;
         const double t = bytes <= conc * tp ? tp : tp + (bytes - conc * tp) / bw;
-        if (t < best_t * 0.995) { best_t = t; best = s; }
+        if (t < best_t * 0.995) { best_t = t; best = eff; }
     }
     return best;
 }
